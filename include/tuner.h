@@ -1,0 +1,189 @@
+/*
+ * tuner.h — C ABI of the MI355X full-space sweep of an ANN performance model.
+ *
+ * Problem wrapped (paper: Falch & Elster, "Machine Learning Based Auto-tuning
+ * for Enhanced OpenCL Performance Portability", Section 5): given the value
+ * lists of P tuning parameters (Section 5.1, Table 2), a trained bagged ensemble
+ * of small sigmoid networks (Section 5.2) and M, predict the (log) execution
+ * time of EVERY configuration of the Cartesian product (Section 5.3, first
+ * paragraph) and return the M configurations with the lowest predictions
+ * (Section 5.3, third paragraph).  Configurations that are statically known to
+ * be invalid (Section 5.2, last paragraph) are masked.
+ *
+ * Conventions
+ *  - Every function returns a status code (TUNER_OK = 0, negative = error),
+ *    never throws or aborts; output parameters are untouched on error.
+ *    tuner_last_error() gives a thread-local message for the last failure.
+ *  - "host" pointers are ordinary CPU memory, read during the call only.
+ *    "DEVICE" pointers are GPU memory owned by the caller (for instance a
+ *    PyTorch tensor's data_ptr()) on the device that is current at call time.
+ *  - The library allocates no device memory: outputs and the workspace are
+ *    caller-allocated.  Work is enqueued on the given HIP stream (a
+ *    hipStream_t passed as void*, NULL = default stream) and the functions
+ *    return without synchronising; results are ready once the stream is.
+ *  - Index order of the Cartesian product: parameter 0 is the most significant
+ *    digit, the last parameter varies fastest.  Indices are < 2^32 on the
+ *    device; spaces of up to exactly 2^32 configurations are accepted.
+ */
+#ifndef TUNER_H_
+#define TUNER_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct tuner_space tuner_space; /* opaque host object */
+
+enum {
+  TUNER_OK = 0,
+  TUNER_EINVAL = -1,     /* null pointer, bad size, bad enum, range outside the space */
+  TUNER_ETOOLARGE = -2,  /* space > 2^32, too many parameters/values/rules, layer too wide, k too large */
+  TUNER_ENOMEM = -3,     /* host allocation failed */
+  TUNER_EWORKSPACE = -4, /* workspace missing or smaller than tuner_workspace_bytes() */
+  TUNER_EHIP = -5        /* a HIP runtime call failed (message has the HIP error string) */
+};
+
+enum { TUNER_SCALE_LINEAR = 0, TUNER_SCALE_LOG2 = 1 };
+enum { TUNER_FP32 = 0, TUNER_BF16_MFMA = 1 };
+/* How the fp32 network is evaluated.  AUTO picks the matrix-core path. */
+enum { TUNER_ALGO_AUTO = 0, TUNER_ALGO_MFMA = 1, TUNER_ALGO_VALU = 2 };
+
+/* Limits of this build. */
+#define TUNER_MAX_PARAMS 31       /* P */
+#define TUNER_MAX_VALUES 256      /* sum of the list lengths */
+#define TUNER_MAX_CONSTRAINTS 8
+#define TUNER_MAX_CONSTRAINT_ENTRIES 64 /* (rule, parameter) pairs with a non-zero term */
+#define TUNER_MAX_TERM_WORDS 256  /* total length of the non-zero term tables */
+#define TUNER_MAX_WIDTH 128       /* hidden-layer width */
+#define TUNER_MAX_K 16384
+
+/*
+ * The ensemble (Section 5.2: k networks, prediction = mean of their outputs;
+ * Section 4.2: a neuron is a weighted sum followed by an activation).  Hidden
+ * layers use the logistic sigmoid 1/(1+exp(-t)), the single output is linear
+ * (it is the predicted log execution time).  Plain data, caller-owned.
+ */
+typedef struct {
+  int32_t n_members;        /* E >= 1 (the paper uses 11) */
+  int32_t n_layers;         /* dense layers including the output layer: 2 or 3 */
+  const int32_t* widths;    /* host, [n_layers+1] = {P, H1, (H2,) 1} */
+  const float* weights_dev; /* DEVICE, fp32, per member and per layer:
+                               W[out][in] row-major, then b[out];
+                               i.e. W1,b1,(W2,b2,)w_o,b_o ; members back to back */
+  int32_t precision;        /* TUNER_FP32 (TUNER_BF16_MFMA is not built yet: EINVAL) */
+  int32_t algo;             /* TUNER_ALGO_* */
+} tuner_model;
+
+/*
+ * Builds the space object (host only; copies every array, so the caller may
+ * free its arrays on return).
+ *   n_params          P, 1..TUNER_MAX_PARAMS
+ *   radices[P]        length of each parameter's value list (>= 1)
+ *   values[sum r]     host, the lists concatenated (Table 2 style)
+ *   scales[P]         TUNER_SCALE_LINEAR: feature = value; TUNER_SCALE_LOG2:
+ *                     feature = log2(value) (values must be > 0); either way
+ *                     min-max normalised to [0,1] over the list, computed in
+ *                     double and rounded once to fp32 (a constant list -> 0)
+ *   n_constraints     C, 0..TUNER_MAX_CONSTRAINTS
+ *   constraint_terms  host, [C][sum r] integer terms T_c, same order as values
+ *   constraint_bounds host, [C]; configuration with digits d is valid iff for
+ *                     every c: sum_p T_c[offset_p + d_p] <= bound_c
+ * Errors: EINVAL (null, radix < 1, bad scale, log2 of a value <= 0, non-finite
+ * value, sum of |terms| not representable in int32), ETOOLARGE (limits above,
+ * or more than 2^32 configurations), ENOMEM.
+ */
+int tuner_space_create(int32_t n_params, const int32_t* radices, const double* values,
+                       const int32_t* scales, int32_t n_constraints,
+                       const int32_t* constraint_terms, const int64_t* constraint_bounds,
+                       tuner_space** out);
+void tuner_space_destroy(tuner_space* space);
+
+/* Number of configurations N = product of the radices (Section 5.1). */
+int tuner_space_size(const tuner_space* space, uint64_t* n_configs);
+
+/*
+ * Host helpers for one configuration.  decode: index -> digits[P], and (if
+ * non-null) values[P] (the parameter values), features[P] (fp32 network
+ * inputs) and *valid (0/1).  encode: digits[P] -> index.  EINVAL if the index
+ * or a digit is out of range.
+ */
+int tuner_space_decode(const tuner_space* space, uint64_t index, int32_t* digits,
+                       double* values, float* features, int32_t* valid);
+int tuner_space_encode(const tuner_space* space, const int32_t* digits, uint64_t* index);
+
+/*
+ * Host check of the device decoder's arithmetic: evaluates, on the CPU, the
+ * very routine the kernels use (multiply-shift division constants, validity
+ * sums in 32 bits).  Used by the CPU tests; same outputs as tuner_space_decode
+ * minus the values.
+ */
+int tuner_space_decode_device_arith(const tuner_space* space, uint64_t index, int32_t* digits,
+                                    float* features, int32_t* valid);
+
+/*
+ * Bytes of DEVICE workspace needed by tuner_predict_topk / tuner_predict_all
+ * for this model and k (k may be 0 for predict_all).  Returns 0 on invalid
+ * arguments (see tuner_last_error).  Does not depend on the index range.
+ */
+size_t tuner_workspace_bytes(const tuner_space* space, const tuner_model* model, int32_t k);
+
+/*
+ * Sweep of indices [index_begin, index_begin + index_count) and selection of
+ * the k valid configurations with the smallest predictions, ordered by
+ * (prediction, then index), ascending (Section 5.3).
+ *   merge_with_existing  0: the outputs are overwritten.  1: the outputs hold
+ *                        the running result of earlier calls (values, indices
+ *                        and *n_found as this function wrote them, same k) and
+ *                        are replaced by the top-k of the union; used to stream
+ *                        a large space chunk by chunk, in any chunk order.
+ *   topk_values_dev      DEVICE, k floats
+ *   topk_indices_dev     DEVICE, k uint32
+ *   n_found_dev          DEVICE, one int32 = min(k, number of valid
+ *                        configurations seen so far); entries past it are
+ *                        (+INF, 0xFFFFFFFF)
+ *   workspace_dev        DEVICE, >= tuner_workspace_bytes(), 256-byte aligned;
+ *                        contents need not be preserved between calls
+ * index_count may be 0 (the result is then the existing one, or empty).
+ * Calls that share a workspace must be ordered on one stream.
+ * Errors: EINVAL (null, k < 1, range outside the space, model/space mismatch,
+ * unsupported precision), ETOOLARGE (k > TUNER_MAX_K, width > TUNER_MAX_WIDTH),
+ * EWORKSPACE, EHIP.
+ */
+int tuner_predict_topk(const tuner_space* space, const tuner_model* model,
+                       uint64_t index_begin, uint64_t index_count, int32_t k,
+                       int32_t merge_with_existing, float* topk_values_dev,
+                       uint32_t* topk_indices_dev, int32_t* n_found_dev, void* workspace_dev,
+                       size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Sweep of the range writing every prediction (Section 5.3, first paragraph).
+ *   predictions_dev  DEVICE, index_count floats; +INF where invalid
+ *   valid_mask_dev   DEVICE, optional (NULL to skip), index_count bytes 0/1
+ */
+int tuner_predict_all(const tuner_space* space, const tuner_model* model, uint64_t index_begin,
+                      uint64_t index_count, float* predictions_dev, uint8_t* valid_mask_dev,
+                      void* workspace_dev, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Decoder output for a range, for checking steps one by one: digits
+ * (DEVICE, [index_count][P] int32, optional), features (DEVICE,
+ * [index_count][P] fp32, optional) and validity (DEVICE, index_count bytes,
+ * optional), produced by the same device routine the sweep uses.
+ */
+int tuner_decode_range(const tuner_space* space, uint64_t index_begin, uint64_t index_count,
+                       int32_t* digits_dev, float* features_dev, uint8_t* valid_mask_dev,
+                       void* hip_stream);
+
+/* Message for the last error on this thread; valid until the next call. */
+const char* tuner_last_error(void);
+
+/* Library version string. */
+const char* tuner_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TUNER_H_ */

@@ -1,0 +1,38 @@
+// Host-side internals shared by the translation units of the library.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "../../include/tuner.h"
+#include "dev_space.h"
+
+struct tuner_space {
+  int32_t n_params = 0;
+  uint64_t n_configs = 0;
+  std::vector<int32_t> radices;
+  std::vector<uint64_t> strides;     // true strides (product of the later radices)
+  std::vector<int64_t> offsets;      // start of each value list
+  std::vector<double> values;
+  std::vector<int32_t> scales;
+  int32_t n_constraints = 0;
+  std::vector<int32_t> terms;        // [C][sum r] as given
+  std::vector<int64_t> bounds;
+  int64_t total_values = 0;
+  tuner::DevSpace dev;               // what the kernels see
+};
+
+namespace tuner {
+
+int set_error(int code, const std::string& msg);
+int hip_error(hipError_t e, const char* what);
+
+#define TUNER_HIP_TRY(expr)                                   \
+  do {                                                        \
+    hipError_t e_ = (expr);                                   \
+    if (e_ != hipSuccess) return tuner::hip_error(e_, #expr); \
+  } while (0)
+
+}  // namespace tuner
