@@ -1,0 +1,152 @@
+#!/usr/bin/env python3
+"""Benchmark of the full-space model sweep on one MI355X.
+
+A step = one pass of the whole hot path (decode, features, validity, ensemble
+MLP, mean, mask, top-k, and for the streamed workload the on-device chunk
+merge) over the whole synthetic space, inputs resident in HBM.  Default
+workload: the 2^27-configuration space with 4 networks 14-64-64-1, k = 1000
+(the configuration the headline metric and target are quoted on).
+
+Prints ONE JSON line (see README for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_FP32_MATRIX_TFLOPS = 157.3   # MI355X published dense fp32 matrix (= fp32 vector) peak
+PEAK_HBM_GBS = 8000.0
+
+
+def cpu_baseline(w, budget_blocks: int):
+    """Times the CPU oracle (as it stands) on evenly spaced aligned blocks of the
+    same workload; returns swept configurations per second."""
+    import numpy as np
+    import oracle
+    sp, m = w.space, w.model
+    n = sp.n_configs
+    block = min(n, 1 << 12)
+    n_blocks_total = n // block
+    nb = min(budget_blocks, n_blocks_total)
+    threads = min(16, os.cpu_count() or 1)
+    # warm (library load, page-in)
+    oracle.predict_range(sp, m, 0, min(block, 256), threads=1)
+    t0 = time.perf_counter()
+    swept = 0
+    evaluated = 0
+    # groups of `threads` blocks are swept concurrently by the oracle's range partitioner
+    step = max(1, n_blocks_total // nb)
+    for b in range(0, nb):
+        begin = (b * step) * block
+        _, valid, _ = oracle.predict_range(sp, m, begin, block, threads=threads)
+        swept += block
+        evaluated += int(valid.sum())
+    dt = time.perf_counter() - t0
+    return {"value": swept / dt, "unit": "configs/s", "cores": threads, "kind": "oracle",
+            "sample": f"{nb} blocks of {block} indices evenly spaced over the space "
+                      f"({swept} swept, {evaluated} valid, {dt:.1f} s)",
+            "evaluated_per_s": evaluated / dt}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cfg3",
+                    help="cfg1..cfg5, cfg3-2^26, paper-convolution, paper-raycasting, paper-stereo")
+    ap.add_argument("--mode", default="topk", choices=["topk", "all"])
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--cpu-blocks", type=int, default=0, help="blocks of 4096 indices for the CPU baseline")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (the sweep shards by index range; "
+              "no multi-GPU path is built). Use --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import workloads as wl
+    import paper_1506_00842_amd as T
+    from paper_1506_00842_amd.api import Sweep
+
+    w = wl.BENCH_WORKLOADS[args.workload]()
+    sp, m = w.space, w.model
+    N = sp.n_configs
+    chunk = w.chunk if w.chunk else N
+    sw = Sweep(sp, m, w.k if args.mode == "topk" else 0)
+    stream = torch.cuda.current_stream()
+    pred = mask = None
+    if args.mode == "all":
+        pred = torch.empty(chunk, dtype=torch.float32, device=sw.device)
+
+    def step():
+        if args.mode == "topk":
+            first = True
+            for b in range(0, N, chunk):
+                sw.topk(b, min(chunk, N - b), merge=not first, stream=stream)
+                first = False
+        else:
+            for b in range(0, N, chunk):
+                sw.predict_all(b, min(chunk, N - b), want_mask=False, out=pred, stream=stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    T.tuner_profile_enable(True)
+    T.tuner_profile_read()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    sweep_ms, n_launch = T.tuner_profile_read()
+    T.tuner_profile_enable(False)
+
+    ms_per_step = 1e3 * dt / args.steps
+    n_valid = w.n_valid if w.n_valid >= 0 else None
+    flop_per_cfg = 2 * m.macs_per_config
+    launches_per_step = n_launch / args.steps
+    kernel_ms = sweep_ms / max(n_launch, 1)
+    roof = None
+    if n_valid is not None:
+        # the sweep skips tiles with no valid configuration: only evaluated
+        # configurations count as algorithmic flops
+        flops_per_launch = n_valid * flop_per_cfg / launches_per_step
+        achieved = flops_per_launch / (kernel_ms * 1e-3) / 1e12
+        roof = {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP32_MATRIX_TFLOPS,
+                "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MATRIX_TFLOPS, "traffic": None,
+                "kernel": "sweep_kernel (fp32 MFMA 32x32x2)", "kernel_ms": kernel_ms,
+                "launches_per_step": launches_per_step,
+                "flop_per_config": flop_per_cfg, "evaluated_configs_per_launch": n_valid / launches_per_step,
+                "sigmoids_per_config": m.sigmoids_per_config}
+    out = {
+        "metric": "predicted configs/sec (decode+MLP ensemble+top-k)" if args.mode == "topk"
+                  else "predicted configs/sec (decode+MLP ensemble, all predictions written)",
+        "value": N / (dt / args.steps), "unit": "configs/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "n_configs": N, "n_valid": n_valid, "k": w.k,
+                   "members": m.n_members, "widths": list(m.widths), "mode": args.mode,
+                   "chunk": chunk},
+        "roofline": roof,
+    }
+    if args.mode == "all":
+        out["hbm_write_GBs"] = 4.0 * N / (dt / args.steps) / 1e9
+    if not args.no_cpu:
+        blocks = args.cpu_blocks or {"cfg1": 1, "cfg2": 96}.get(args.workload, 0)
+        if not blocks:
+            # aim at roughly 15 s: ~1.2e9 flop/s/core in double with exp
+            est_cfg_per_s = 16 * 1.0e9 / max(flop_per_cfg, 1)
+            blocks = max(16, int(15 * est_cfg_per_s / 4096))
+        out["cpu_baseline"] = cpu_baseline(w, blocks)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -177,6 +177,16 @@ int tuner_decode_range(const tuner_space* space, uint64_t index_begin, uint64_t 
                        int32_t* digits_dev, float* features_dev, uint8_t* valid_mask_dev,
                        void* hip_stream);
 
+/*
+ * Timing of the dominant kernel (the fused sweep) for roofline reports.  While
+ * enabled, every predict call brackets its sweep kernel with a pair of HIP
+ * events on the caller's stream.  tuner_profile_read waits for the recorded
+ * events, returns the summed kernel time in milliseconds and the number of
+ * launches, and forgets them.  Process-wide, not thread-safe; off by default.
+ */
+int tuner_profile_enable(int32_t on);
+int tuner_profile_read(double* sweep_ms_total, int64_t* n_sweep_launches);
+
 /* Message for the last error on this thread; valid until the next call. */
 const char* tuner_last_error(void);
 

@@ -92,6 +92,21 @@ def predict_range(space, model, begin: int, count: int, threads: int = 1,
     return yhat, valid, digs
 
 
+def predict_indices(space, model, indices, threads: int = 1):
+    """Returns (yhat fp32[n], valid u8[n]) for an arbitrary list of indices."""
+    keep, a = _space_args(space)
+    idx = np.ascontiguousarray(indices, dtype=np.uint64)
+    yhat = np.empty(len(idx), np.float32)
+    valid = np.empty(len(idx), np.uint8)
+    widths = np.ascontiguousarray(model.widths, dtype=np.int32)
+    w = np.ascontiguousarray(model.weights, dtype=np.float32)
+    lib().oracle_predict_indices(*a, C.c_int(int(model.n_members)), C.c_int(len(widths) - 1),
+                                 _p(widths, C.c_int32), _p(w, C.c_float), _p(idx, C.c_uint64),
+                                 C.c_uint64(len(idx)), _p(yhat, C.c_float), _p(valid, C.c_uint8),
+                                 C.c_int(threads))
+    return yhat, valid
+
+
 def select_topk(yhat, valid, index_base: int, k: int):
     """k smallest (value, index) among valid entries, ascending."""
     yhat = np.ascontiguousarray(yhat, dtype=np.float32)

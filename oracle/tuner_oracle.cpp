@@ -212,6 +212,30 @@ int oracle_predict_range(int n_params, const int32_t* radices, const double* val
   return 0;
 }
 
+// Same as oracle_predict_range for an arbitrary list of indices.
+int oracle_predict_indices(int n_params, const int32_t* radices, const double* values,
+                           const int32_t* scales, int n_constraints, const int32_t* terms,
+                           const int64_t* bounds, int n_members, int n_layers,
+                           const int32_t* widths, const float* weights, const uint64_t* indices,
+                           uint64_t count, float* yhat, uint8_t* valid, int n_threads) {
+  SpaceView s{n_params, radices, values, scales, n_constraints, terms, bounds, {}, {}, 0};
+  build_lut(s);
+  if (n_threads < 1) n_threads = 1;
+  std::vector<std::thread> pool;
+  const uint64_t per = (count + n_threads - 1) / n_threads;
+  for (int t = 0; t < n_threads; ++t) {
+    const uint64_t lo = std::min<uint64_t>(count, per * t), hi = std::min<uint64_t>(count, lo + per);
+    if (hi <= lo) continue;
+    pool.emplace_back([&, lo, hi] {
+      for (uint64_t j = lo; j < hi; ++j)
+        predict_range(s, n_members, n_layers, widths, weights, indices[j], 1, yhat + j,
+                      valid + j, nullptr);
+    });
+  }
+  for (auto& th : pool) th.join();
+  return 0;
+}
+
 // Selection from given predictions: the k smallest (value, index) pairs among
 // entries with valid[t] != 0, ascending; index reported = index_base + t.
 // Bounded max-heap; returns the number found (min(k, #valid)).

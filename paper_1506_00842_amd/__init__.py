@@ -28,7 +28,7 @@ EXPORTS = [
     "tuner_space_create", "tuner_space_destroy", "tuner_space_size", "tuner_space_decode",
     "tuner_space_encode", "tuner_space_decode_device_arith", "tuner_workspace_bytes",
     "tuner_predict_topk", "tuner_predict_all", "tuner_decode_range", "tuner_last_error",
-    "tuner_version",
+    "tuner_version", "tuner_profile_enable", "tuner_profile_read",
 ]
 
 
@@ -93,6 +93,17 @@ def _check(rc: int):
 
 def tuner_last_error() -> str:
     return load_library().tuner_last_error().decode()
+
+
+def tuner_profile_enable(on: bool) -> None:
+    _check(load_library().tuner_profile_enable(1 if on else 0))
+
+
+def tuner_profile_read():
+    """-> (summed sweep-kernel milliseconds, number of launches) since the last read."""
+    ms = C.c_double(); n = C.c_int64()
+    _check(load_library().tuner_profile_read(C.byref(ms), C.byref(n)))
+    return float(ms.value), int(n.value)
 
 
 def tuner_version() -> str:

@@ -20,6 +20,8 @@
 // with -log2(e) folded into the packed weights: sigma(z) = 1 / (1 + 2^(z')).
 #include <cstdio>
 #include <cstring>
+#include <utility>
+#include <vector>
 
 #include "tuner_internal.h"
 
@@ -569,6 +571,13 @@ static const Variant* find_variant(Shape* sh) {
   return nullptr;
 }
 
+// Optional timing of the sweep kernel alone (HIP events on the caller's stream).
+struct ProfileState {
+  bool on = false;
+  std::vector<std::pair<hipEvent_t, hipEvent_t>> events;
+};
+static ProfileState g_profile;
+
 struct DeviceInfo { int n_cu = 0; int max_lds = 0; bool ok = false; };
 
 static int device_info(DeviceInfo* out) {
@@ -660,8 +669,18 @@ static int run_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin
     const size_t lds = (size_t)kSpaceBytes + (size_t)mps * member_bytes;
     TUNER_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(var->fn),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipEvent_t ev0 = nullptr, ev1 = nullptr;
+    if (g_profile.on) {
+      TUNER_HIP_TRY(hipEventCreate(&ev0));
+      TUNER_HIP_TRY(hipEventCreate(&ev1));
+      TUNER_HIP_TRY(hipEventRecord(ev0, stream));
+    }
     hipLaunchKernelGGL(var->fn, dim3(groups), dim3(kThreads), lds, stream, sw, sh.o_w2, sh.o_b2, sh.o_wo);
     TUNER_HIP_TRY(hipGetLastError());
+    if (g_profile.on) {
+      TUNER_HIP_TRY(hipEventRecord(ev1, stream));
+      g_profile.events.emplace_back(ev0, ev1);
+    }
   }
 
   if (mode == MODE_TOPK) {
@@ -695,6 +714,30 @@ size_t tuner_workspace_bytes(const tuner_space* space, const tuner_model* model,
   if (tuner::make_shape(space, model, &sh)) return 0;
   if (!tuner::find_variant(&sh)) { set_error(TUNER_ETOOLARGE, "no kernel variant for this model shape"); return 0; }
   return tuner::make_layout(sh, k).total;
+}
+
+int tuner_profile_enable(int32_t on) {
+  tuner::g_profile.on = on != 0;
+  return TUNER_OK;
+}
+
+int tuner_profile_read(double* sweep_ms_total, int64_t* n_sweep_launches) {
+  if (!sweep_ms_total || !n_sweep_launches) return set_error(TUNER_EINVAL, "null argument");
+  double total = 0.0;
+  int64_t n = 0;
+  for (auto& ev : tuner::g_profile.events) {
+    float ms = 0.0f;
+    TUNER_HIP_TRY(hipEventSynchronize(ev.second));
+    TUNER_HIP_TRY(hipEventElapsedTime(&ms, ev.first, ev.second));
+    total += ms;
+    ++n;
+    hipEventDestroy(ev.first);
+    hipEventDestroy(ev.second);
+  }
+  tuner::g_profile.events.clear();
+  *sweep_ms_total = total;
+  *n_sweep_launches = n;
+  return TUNER_OK;
 }
 
 int tuner_predict_topk(const tuner_space* space, const tuner_model* model, uint64_t index_begin,

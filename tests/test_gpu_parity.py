@@ -1,0 +1,263 @@
+"""GPU parity tests: the HIP path (through the C ABI) against the CPU oracle on
+the same seeded inputs.  Decoded digits, features and the validity mask are
+compared bit for bit; predictions within 1e-5 (scaled, see parity.py); top-k by
+the band rule.  Run with -m gpu on an MI355X."""
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+import parity
+import workloads as wl
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+THREADS = min(16, os.cpu_count() or 1)
+
+
+def sweep_for(w, k=None, **kw):
+    from paper_1506_00842_amd.api import Sweep
+    return Sweep(w.space, w.model, w.k if k is None else k, **kw)
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+# ------------------------------------------------------------------ decode ---
+DECODE_CASES = [
+    (wl.tiny, 0, 256), (wl.conv_shaped, 0, 393216), (wl.paper_raycasting, 655360 - 70001, 70001),
+    (wl.paper_stereo, 1234567, 99999), (wl.large, (1 << 27) - 100003, 100003),
+    (wl.streamed, (1 << 32) - 65539, 65539), (wl.streamed, (1 << 31) - 777, 5000),
+    (lambda: wl.random_small(5), 0, None), (lambda: wl.many_params(25, [8], 1, 3), 188743680 - 50000, 50000),
+]
+
+
+@pytest.mark.parametrize("maker,begin,count", DECODE_CASES)
+def test_decode_features_mask_bit_exact(maker, begin, count):
+    w = maker()
+    sp = w.space
+    count = sp.n_configs if count is None else count
+    say("decode", sp.name, begin, count)
+    sw = sweep_for(w, k=0)
+    d, f, v = sw.decode(begin, count)
+    torch.cuda.synchronize()
+    _, ov, od = oracle.predict_range(sp, None, begin, count, threads=THREADS, want_yhat=False, want_digits=True)
+    assert np.array_equal(d.cpu().numpy(), od)
+    assert np.array_equal(v.cpu().numpy(), ov)
+    lut = oracle.feature_lut(sp)
+    of = np.stack([lut[sp.offsets[p] + od[:, p]] for p in range(sp.n_params)], axis=1)
+    assert np.array_equal(f.cpu().numpy(), of)
+
+
+# ------------------------------------------------------------ predict_all ----
+def _check_range(w, begin, count, sw=None):
+    sp, m = w.space, w.model
+    sw = sw or sweep_for(w, k=0)
+    pred, mask = sw.predict_all(begin, count)
+    torch.cuda.synchronize()
+    oy, ov, _ = oracle.predict_range(sp, m, begin, count, threads=THREADS)
+    assert np.array_equal(mask.cpu().numpy(), ov)
+    worst, rel = parity.check_predictions(pred.cpu().numpy(), oy, ov)
+    say(f"  {w.name} [{begin}, +{count}): worst {worst:.3f} x tol, pure-relative worst {rel:.2e}")
+
+
+def test_predict_all_tiny_and_conv_full():
+    for maker in (wl.tiny, wl.conv_shaped):
+        w = maker()
+        _check_range(w, 0, w.space.n_configs)
+
+
+@pytest.mark.parametrize("maker", [wl.paper_convolution, wl.paper_raycasting, wl.paper_stereo])
+def test_predict_all_paper_spaces_full(maker):
+    w = maker()
+    _check_range(w, 0, w.space.n_configs)
+
+
+SHAPES = [  # (n_params, hidden widths, members): every kernel family and padding
+    (3, [5], 1), (7, [30], 11), (7, [33], 2), (9, [64], 3), (12, [100], 2), (15, [128], 2),
+    (16, [20], 3), (23, [32], 2), (24, [64], 2), (31, [17], 2),
+    (5, [7, 7], 2), (10, [32, 32], 3), (14, [40, 20], 3), (14, [20, 60], 2), (14, [64, 64], 4),
+    (14, [128, 128], 3), (14, [100, 70], 2), (20, [64, 64], 8), (26, [33, 31], 2), (31, [128, 100], 2),
+]
+
+
+@pytest.mark.parametrize("P,hidden,E", SHAPES)
+def test_predict_all_model_shapes(P, hidden, E):
+    w = wl.many_params(P, hidden, E, seed=100 + P + len(hidden))
+    n = w.space.n_configs
+    count = min(n, 20011)                      # ragged: not a multiple of the tile or chunk
+    begin = 0 if n == count else (n // 3) | 1
+    _check_range(w, begin, count)
+    wp = wl.many_params(P, hidden, E, seed=7, pow2=True)
+    n = wp.space.n_configs
+    count = min(n, 9001)
+    _check_range(wp, n - count, count)
+
+
+def test_predict_all_ragged_and_empty_ranges():
+    w = wl.conv_shaped()
+    sw = sweep_for(w, k=0)
+    for begin, count in ((0, 1), (31, 2), (1023, 1026), (393216 - 1, 1), (5000, 4097), (77, 31)):
+        _check_range(w, begin, count, sw)
+    # empty range: nothing is written
+    out = torch.full((8,), -1.0, device="cuda")
+    sw.predict_all(100, 0, want_mask=False, out=out)
+    torch.cuda.synchronize()
+    assert torch.all(out == -1.0)
+
+
+def test_predict_all_large_and_wide_slices():
+    for maker, count in ((wl.large, 1 << 18), (wl.wide, 1 << 15), (wl.streamed, 1 << 17)):
+        w = maker()
+        sw = sweep_for(w, k=0)
+        n = w.space.n_configs
+        # slices that contain both valid and invalid blocks
+        for begin in (0, (37 << 15) + 4321, n - count):
+            _check_range(w, begin, count, sw)
+
+
+def test_saturation_zero_weights_and_constant_net():
+    w = wl.conv_shaped()
+    m = w.model
+    z = wl.Model(m.widths, m.n_members, np.zeros_like(m.weights))
+    fpm = z.floats_per_member
+    for e in range(z.n_members):
+        z.weights[(e + 1) * fpm - 1] = 0.5 * (e + 1)
+    wz = wl.Workload("zero", w.space, z, 25)
+    sw = sweep_for(wz)
+    pred, mask = sw.predict_all(0, 50000)
+    sw.topk(0, w.space.n_configs)
+    torch.cuda.synchronize()
+    g = pred.cpu().numpy()
+    ok = mask.cpu().numpy().astype(bool)
+    assert np.all(g[ok] == np.float32(0.5 * 36 / 8))          # mean of the output biases
+    # all predictions equal: the k smallest are the first k valid indices
+    _, ov, _ = oracle.predict_range(w.space, None, 0, 5000, want_yhat=False)
+    gv, gi = sw.topk_host()
+    assert list(gi) == list(np.nonzero(ov)[0][:25])
+    # saturated sigmoids stay finite
+    big = wl.Model(m.widths, 1, np.zeros(fpm, np.float32))
+    (W1, b1), (wo, bo) = big.member_layers(0)
+    b1[:15] = 1e4
+    b1[15:] = -1e4
+    wo[:] = 1.0
+    sw2 = sweep_for(wl.Workload("sat", w.space, big, 5))
+    pred, mask = sw2.predict_all(0, 4096)
+    torch.cuda.synchronize()
+    g = pred.cpu().numpy()[mask.cpu().numpy().astype(bool)]
+    assert np.all(g == 15.0)
+
+
+# ------------------------------------------------------------------- top-k ---
+def test_topk_small_spaces_exact_and_band():
+    for maker in (wl.tiny, wl.conv_shaped, lambda: wl.random_small(2), lambda: wl.random_small(4),
+                  wl.paper_convolution):
+        w = maker()
+        sp = w.space
+        n = sp.n_configs
+        oy, ov, _ = oracle.predict_range(sp, w.model, 0, n, threads=THREADS)
+        n_valid = int(ov.sum())
+        for k in sorted({1, 2, w.k, 1000, max(1, n_valid), n_valid + 3}):
+            if k > 16384:
+                continue
+            sw = sweep_for(w, k=k)
+            sw.topk(0, n)
+            torch.cuda.synchronize()
+            gv, gi = sw.topk_host()
+            parity.check_topk(gv, gi, oy, ov, 0, k)
+            # tail entries past n_found are (+inf, 0xFFFFFFFF)
+            nf = len(gi)
+            if nf < k:
+                assert torch.all(torch.isposinf(sw.values[nf:]))
+                assert torch.all(sw.indices[nf:] == -1)
+            say(f"  {w.name} k={k}: n_found {nf}")
+
+
+def test_topk_unconstrained_is_the_papers_unmasked_sweep():
+    w = wl.conv_shaped()
+    wu = wl.Workload("u", w.space.without_constraints(), w.model, w.k)
+    n = wu.space.n_configs
+    oy, ov, _ = oracle.predict_range(wu.space, wu.model, 0, n, threads=THREADS)
+    assert ov.all()
+    sw = sweep_for(wu)
+    sw.topk(0, n)
+    torch.cuda.synchronize()
+    gv, gi = sw.topk_host()
+    parity.check_topk(gv, gi, oy, ov, 0, wu.k)
+
+
+def test_topk_chunked_merge_equals_one_call_any_order():
+    w = wl.paper_raycasting()
+    sp = w.space
+    n = sp.n_configs
+    sw = sweep_for(w)
+    sw.topk(0, n)
+    torch.cuda.synchronize()
+    ref_v, ref_i = sw.topk_host()
+    oy, ov, _ = oracle.predict_range(sp, w.model, 0, n, threads=THREADS)
+    parity.check_topk(ref_v, ref_i, oy, ov, 0, w.k)
+    bounds = [0, 1000, 1031, 200000, 200001, 500000, n]
+    chunks = list(zip(bounds[:-1], bounds[1:]))
+    for order in (list(range(len(chunks))), [5, 0, 3, 1, 4, 2]):
+        sw2 = sweep_for(w)
+        first = True
+        for j in order:
+            b, e = chunks[j]
+            sw2.topk(b, e - b, merge=not first)
+            first = False
+        torch.cuda.synchronize()
+        v, i = sw2.topk_host()
+        # same kernels, same values: the merged result is bit-identical
+        assert np.array_equal(i, ref_i) and np.array_equal(v, ref_v)
+    # empty chunk keeps the running result; a fresh empty call gives an empty result
+    sw2.topk(5, 0, merge=True)
+    torch.cuda.synchronize()
+    v, i = sw2.topk_host()
+    assert np.array_equal(i, ref_i)
+    sw2.topk(5, 0, merge=False)
+    torch.cuda.synchronize()
+    assert int(sw2.n_found.item()) == 0
+
+
+def test_topk_repeatable_and_k_max():
+    w = wl.conv_shaped()
+    n = w.space.n_configs
+    sw = sweep_for(w, k=16384)
+    res = []
+    for _ in range(3):
+        sw.topk(0, n)
+        torch.cuda.synchronize()
+        res.append(sw.topk_host())
+    for v, i in res[1:]:
+        assert np.array_equal(i, res[0][1]) and np.array_equal(v, res[0][0])
+    oy, ov, _ = oracle.predict_range(w.space, w.model, 0, n, threads=THREADS)
+    parity.check_topk(res[0][0], res[0][1], oy, ov, 0, 16384)
+
+
+def test_adversarial_order_descending_predictions():
+    """Predictions that decrease with the index make every configuration pass
+    the running threshold: exercises pool compaction under maximum pressure."""
+    sp = wl.Space("desc", [[float(v) for v in range(1, 65)]] * 3, [wl.SCALE_LINEAR] * 3)
+    # y = -(256 sigmoid(2 x0) + sigmoid(2 x1)): non-increasing in the index, and every
+    # new (x0, x1) group lies below everything seen before it
+    m = wl.make_model([3, 8, 1], 1, 0)
+    (Wh, bh), (wo, bo) = m.member_layers(0)
+    Wh[:] = 0.0
+    bh[:] = 0.0
+    wo[:] = 0.0
+    Wh[0, 0] = 2.0
+    Wh[1, 1] = 2.0
+    wo[0, 0] = -256.0
+    wo[0, 1] = -1.0
+    w = wl.Workload("desc", sp, m, 1000)
+    n = sp.n_configs
+    oy, ov, _ = oracle.predict_range(sp, m, 0, n, threads=THREADS)
+    assert np.all(np.diff(oy.astype(np.float64)) <= 0)
+    sw = sweep_for(w)
+    sw.topk(0, n)
+    torch.cuda.synchronize()
+    gv, gi = sw.topk_host()
+    parity.check_topk(gv, gi, oy, ov, 0, 1000)

@@ -1,0 +1,188 @@
+"""CPU tests of the HIP library's host side: the C ABI loads and exports every
+declared symbol, argument validation, space tables, and the device decoder's
+arithmetic evaluated on the host (no kernel is launched here)."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+import workloads as wl
+import paper_1506_00842_amd as T
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def make_space(sp):
+    return T.tuner_space_create(sp.radices, sp.flat_values, sp.scales, sp.constraint_terms,
+                                sp.constraint_bounds)
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "tuner.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    names = set(re.findall(r"\b(tuner_[a-z_0-9]+)\s*\(", hdr))
+    assert {"tuner_space_create", "tuner_predict_topk", "tuner_predict_all"} <= names
+    L = T.load_library()
+    for n in sorted(names):
+        assert hasattr(L, n), f"{n} declared in tuner.h but not exported"
+    assert set(T.EXPORTS) == names
+    assert "gfx950" in T.tuner_version()
+
+
+def test_space_size_and_limits():
+    for maker, n in ((wl.tiny, 256), (wl.conv_shaped, 393216), (wl.large, 1 << 27),
+                     (wl.streamed, 1 << 32), (wl.paper_stereo, 2359296)):
+        assert T.tuner_space_size(make_space(maker().space)) == n
+    with pytest.raises(T.TunerError) as e:                     # 2^33 configurations
+        T.tuner_space_create([2] * 31 + [4], [0.0, 1.0] * 31 + [1.0, 2.0, 3.0, 4.0], [0] * 32)
+    assert e.value.code == T.TUNER_ETOOLARGE
+    with pytest.raises(T.TunerError) as e:                     # exactly 2^32 + something
+        T.tuner_space_create([65536, 65537], list(range(65536 + 65537)), [0, 0])
+    assert e.value.code == T.TUNER_ETOOLARGE
+    with pytest.raises(T.TunerError) as e:
+        T.tuner_space_create([2, 0], [0.0, 1.0], [0, 0])
+    assert e.value.code == T.TUNER_EINVAL
+    with pytest.raises(T.TunerError) as e:
+        T.tuner_space_create([2], [0.0, 1.0], [1])             # log2(0)
+    assert e.value.code == T.TUNER_EINVAL
+    with pytest.raises(T.TunerError) as e:
+        T.tuner_space_create([2], [1.0, 2.0], [7])             # bad scale flag
+    assert e.value.code == T.TUNER_EINVAL
+    with pytest.raises(T.TunerError) as e:
+        T.tuner_space_create([2], [1.0, float("nan")], [0])
+    assert e.value.code == T.TUNER_EINVAL
+    with pytest.raises(T.TunerError) as e:                     # rule sum overflows int32
+        T.tuner_space_create([2, 2], [0, 1, 0, 1], [0, 0],
+                             np.array([[2**31 - 1, 0, 2**31 - 1, 0]], np.int32), [0])
+    assert e.value.code == T.TUNER_EINVAL
+    with pytest.raises(T.TunerError) as e:
+        T.tuner_space_create([300], list(range(300)), [0])
+    assert e.value.code == T.TUNER_ETOOLARGE
+    assert "too many values" in T.tuner_last_error()
+
+
+def _irregular_spaces():
+    yield wl.Space("odd", [[1.0, 2.0, 3.0], [5.0], [1.0, 2.0, 4.0, 8.0, 16.0], [0.0, 1.0],
+                           [float(v) for v in range(1, 8)], [3.0, 9.0, 27.0]],
+                   [0, 1, 1, 0, 0, 1],
+                   np.array([[0, 1, 2, 0, 0, 1, 2, 3, 4, 0, 0] + [0] * 7 + [0, 0, 0],
+                             [0] * 11 + [-3, -2, -1, 0, 1, 2, 3] + [5, 0, -5]], np.int32),
+                   np.array([4, 1], np.int64))
+    yield wl.Space("big-radices", [[float(v) for v in range(1, 251)], [1.0], [1.0, 2.0]],
+                   [1, 0, 0])
+    yield wl.Space("single", [[float(v) for v in range(1, 98)]], [0])
+    for maker in (wl.paper_raycasting, wl.paper_stereo, wl.conv_shaped, wl.large, wl.streamed):
+        yield maker().space
+    for seed in (1, 2, 3, 4, 5, 6, 7):
+        yield wl.random_small(seed).space
+
+
+@pytest.mark.parametrize("sp", list(_irregular_spaces()), ids=lambda s: s.name)
+def test_device_decoder_arithmetic_matches_oracle(sp):
+    """digits, fp32 features and validity computed with the kernels' own
+    multiply-shift routine (on the host) == the oracle's plain division."""
+    h = make_space(sp)
+    n = sp.n_configs
+    st = wl.Stream(99)
+    idx = [0, 1, n - 1, n // 2] + [int(v) for v in st.integers(1500, n)]
+    if n <= 4096:
+        idx = list(range(n))
+    lut = oracle.feature_lut(sp)
+    off = sp.offsets
+    for i in idx:
+        _, ov, od = oracle.predict_range(sp, None, i, 1, want_yhat=False, want_digits=True)
+        d1, vals, f1, ok1 = T.tuner_space_decode(h, i)
+        d2, f2, ok2 = T.tuner_space_decode_device_arith(h, i)
+        assert np.array_equal(d1, od[0]) and np.array_equal(d2, od[0])
+        assert ok1 == bool(ov[0]) and ok2 == bool(ov[0])
+        expect_f = np.array([lut[off[p] + od[0][p]] for p in range(sp.n_params)], np.float32)
+        assert np.array_equal(f1, expect_f) and np.array_equal(f2, expect_f)
+        assert list(vals) == [sp.values[p][od[0][p]] for p in range(sp.n_params)]
+        assert T.tuner_space_encode(h, d1) == i
+
+
+def test_decode_encode_errors():
+    h = make_space(wl.tiny().space)
+    with pytest.raises(T.TunerError):
+        T.tuner_space_decode(h, 256)
+    with pytest.raises(T.TunerError):
+        T.tuner_space_encode(h, [0, 0, 2, 0])
+    with pytest.raises(T.TunerError):
+        T.tuner_space_encode(h, [0, -1, 0, 0])
+
+
+def test_bounds_outside_int32_are_clamped_not_wrapped():
+    vals = [[0.0, 1.0], [0.0, 1.0]]
+    terms = np.array([[0, 1, 0, 1], [0, 1, 0, 1]], np.int32)
+    sp = wl.Space("clamp", vals, [0, 0], terms, np.array([2**40, -2**40], np.int64))
+    h = make_space(sp)
+    for i in range(4):
+        assert T.tuner_space_decode(h, i)[3] is False              # second rule can never hold
+        assert T.tuner_space_decode_device_arith(h, i)[2] is False
+    sp2 = wl.Space("clamp2", vals, [0, 0], terms[:1], np.array([2**40], np.int64))
+    h2 = make_space(sp2)
+    assert all(T.tuner_space_decode_device_arith(h2, i)[2] for i in range(4))
+
+
+class _FakeWeights:
+    """Stands in for a device tensor where no kernel will be launched."""
+
+    def data_ptr(self):
+        return 0x1000
+
+
+def test_workspace_bytes_and_model_validation():
+    w = wl.large()
+    h = make_space(w.space)
+    m = T.ModelHandle(w.model.n_members, w.model.widths, _FakeWeights())
+    b0 = T.tuner_workspace_bytes(h, m, 0)
+    b1 = T.tuner_workspace_bytes(h, m, 1000)
+    b2 = T.tuner_workspace_bytes(h, m, 4096)
+    assert 0 < b0 < b1 < b2 and b0 % 256 == 0
+    for bad, code in (
+        (T.ModelHandle(4, [13, 64, 64, 1], _FakeWeights()), None),        # input width != P
+        (T.ModelHandle(4, [14, 64, 64, 2], _FakeWeights()), None),        # output width != 1
+        (T.ModelHandle(4, [14, 64, 64, 64, 1], _FakeWeights()), None),    # too deep
+        (T.ModelHandle(0, [14, 64, 1], _FakeWeights()), None),            # no members
+        (T.ModelHandle(4, [14, 300, 1], _FakeWeights()), None),           # too wide
+        (T.ModelHandle(4, [14, 64, 1], _FakeWeights(), precision=T.TUNER_BF16_MFMA), None),
+    ):
+        with pytest.raises(T.TunerError):
+            T.tuner_workspace_bytes(h, bad, 10)
+    with pytest.raises(T.TunerError):
+        T.tuner_workspace_bytes(h, m, T.TUNER_MAX_K + 1)
+
+
+def test_predict_argument_errors_before_any_gpu_work():
+    """Invalid calls are rejected on the host (no HIP call is reached)."""
+    L = T.load_library()
+    w = wl.tiny()
+    h = make_space(w.space)
+    m = T.ModelHandle(1, w.model.widths, _FakeWeights())
+    fake = C.c_void_p(0x2000)
+    # null outputs
+    assert L.tuner_predict_topk(h.ptr, C.byref(m.c), 0, 256, 10, 0, None, fake, fake, fake, 1 << 30, None) == T.TUNER_EINVAL
+    # k out of range
+    assert L.tuner_predict_topk(h.ptr, C.byref(m.c), 0, 256, 0, 0, fake, fake, fake, fake, 1 << 30, None) == T.TUNER_EINVAL
+    assert L.tuner_predict_topk(h.ptr, C.byref(m.c), 0, 256, T.TUNER_MAX_K + 1, 0, fake, fake, fake, fake, 1 << 30, None) == T.TUNER_ETOOLARGE
+    # range outside the space
+    assert L.tuner_predict_topk(h.ptr, C.byref(m.c), 200, 57, 10, 0, fake, fake, fake, fake, 1 << 30, None) == T.TUNER_EINVAL
+    assert L.tuner_predict_all(h.ptr, C.byref(m.c), 257, 0, fake, None, fake, 1 << 30, None) == T.TUNER_EINVAL
+    # workspace missing / too small / misaligned
+    need = T.tuner_workspace_bytes(h, m, 10)
+    assert L.tuner_predict_topk(h.ptr, C.byref(m.c), 0, 256, 10, 0, fake, fake, fake, None, need, None) == T.TUNER_EWORKSPACE
+    assert L.tuner_predict_topk(h.ptr, C.byref(m.c), 0, 256, 10, 0, fake, fake, fake, fake, need - 1, None) == T.TUNER_EWORKSPACE
+    assert L.tuner_predict_topk(h.ptr, C.byref(m.c), 0, 256, 10, 0, fake, fake, fake, C.c_void_p(0x2010), need, None) == T.TUNER_EWORKSPACE
+    assert "workspace" in T.tuner_last_error()
+    assert L.tuner_decode_range(h.ptr, 0, 257, None, None, None, None) == T.TUNER_EINVAL
+    assert L.tuner_decode_range(None, 0, 1, None, None, None, None) == T.TUNER_EINVAL
+
+
+def test_binding_fails_loudly_without_the_library(monkeypatch):
+    monkeypatch.setattr(T, "_lib", None)
+    monkeypatch.setattr(T, "LIB_PATH", "/nonexistent/libtuner_hip.so")
+    with pytest.raises(ImportError):
+        T.load_library()

@@ -377,6 +377,27 @@ def random_small(seed: int, max_configs: int = 1024, n_hidden_layers: int = 1,
     return Workload(sp.name, sp, make_model(widths, n_members, seed), k)
 
 
+def many_params(n_params: int, widths_hidden: Sequence[int], n_members: int, seed: int,
+                k: int = 50, pow2: bool = False) -> Workload:
+    """A space with many parameters (radices 3, 5, 2, 2, ... or all 2) to reach
+    the wider input paddings of the kernels; one random small-integer rule."""
+    radices = [2] * n_params
+    if not pow2:
+        radices[0] = 3
+        if n_params > 1:
+            radices[1] = 5
+        if n_params > 4:
+            radices[4] = 3
+    values = [[float(j + 1) for j in range(r)] for r in radices]
+    scales = [SCALE_LOG2 if p % 3 == 0 else SCALE_LINEAR for p in range(n_params)]
+    st = Stream(seed ^ 0x5EED)
+    total = sum(radices)
+    terms = (st.integers(total, 5).astype(np.int64) - 2).astype(np.int32)[None, :]
+    bounds = np.array([n_params // 3], np.int64)
+    sp = Space(f"many-{n_params}-{'pow2' if pow2 else 'mixed'}", values, scales, terms, bounds)
+    return Workload(sp.name, sp, make_model([n_params, *widths_hidden, 1], n_members, seed), k)
+
+
 BENCH_WORKLOADS = {
     "cfg1": tiny, "cfg2": conv_shaped, "cfg3": large, "cfg4": wide, "cfg5": streamed,
     "cfg3-2^26": large_as_written,
