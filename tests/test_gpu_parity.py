@@ -89,7 +89,7 @@ def test_predict_all_model_shapes(P, hidden, E):
     w = wl.many_params(P, hidden, E, seed=100 + P + len(hidden))
     n = w.space.n_configs
     count = min(n, 20011)                      # ragged: not a multiple of the tile or chunk
-    begin = 0 if n == count else (n // 3) | 1
+    begin = min((n // 3) | 1, n - count)
     _check_range(w, begin, count)
     wp = wl.many_params(P, hidden, E, seed=7, pow2=True)
     n = wp.space.n_configs

@@ -382,6 +382,8 @@ def many_params(n_params: int, widths_hidden: Sequence[int], n_members: int, see
     """A space with many parameters (radices 3, 5, 2, 2, ... or all 2) to reach
     the wider input paddings of the kernels; one random small-integer rule."""
     radices = [2] * n_params
+    if n_params > 29:
+        pow2 = True           # 45 * 2**(P-3) would exceed 2**32
     if not pow2:
         radices[0] = 3
         if n_params > 1:
