@@ -63,6 +63,9 @@ def main():
                     help="cfg1..cfg5, cfg3-2^26, paper-convolution, paper-raycasting, paper-stereo")
     ap.add_argument("--mode", default="topk", choices=["topk", "all"])
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--copy-calibration-mib", type=int, default=0,
+                    help="also run one plain device copy of this many MiB (a kernel of known HBM "
+                         "traffic, to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     ap.add_argument("--cpu-blocks", type=int, default=0, help="blocks of 4096 indices for the CPU baseline")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -95,6 +98,13 @@ def main():
             for b in range(0, N, chunk):
                 sw.predict_all(b, min(chunk, N - b), want_mask=False, out=pred, stream=stream)
 
+    if args.copy_calibration_mib:
+        src = torch.ones(args.copy_calibration_mib << 18, dtype=torch.float32, device=sw.device)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()

@@ -27,7 +27,7 @@
 
 namespace tuner {
 
-constexpr int kThreads = 512;             // 8 waves per workgroup, one workgroup per CU
+constexpr int kThreads = 1024;            // 16 waves per workgroup, one workgroup per CU
 constexpr int kWaves = kThreads / 64;
 constexpr int kMaxGroups = 256;           // persistent workgroups (MI355X: 256 CUs)
 constexpr unsigned long long kKeyMax = ~0ull;
@@ -59,6 +59,7 @@ struct SweepParams {
   uint32_t n_chunks;
   int32_t n_members, members_per_stage, n_stages, member_floats;
   int32_t mode, k;
+  float inv_members;          // 1 / n_members, rounded once from double
   uint32_t cap, kp;           // pool capacity per workgroup, k rounded up to a power of two
   const DevSpace* space;      // in the workspace
   const float* packed;
@@ -282,6 +283,21 @@ __device__ void bitonic_sort(unsigned long long* a, uint32_t n, int tid) {
   }
 }
 
+// Sorts pool[0..n2) (n2 a power of two) ascending: in LDS scratch when it fits
+// (lds_entries = capacity of the scratch in keys), else in place in global memory.
+__device__ void sort_pool(unsigned long long* pool, uint32_t n2, unsigned long long* lds,
+                          uint32_t lds_entries, int tid) {
+  if (n2 <= lds_entries) {
+    for (uint32_t x = tid; x < n2; x += kThreads) lds[x] = pool[x];
+    __syncthreads();
+    bitonic_sort(lds, n2, tid);
+    for (uint32_t x = tid; x < n2; x += kThreads) pool[x] = lds[x];
+    __syncthreads();
+  } else {
+    bitonic_sort(pool, n2, tid);
+  }
+}
+
 __device__ __forceinline__ uint32_t next_pow2(uint32_t v) {
   uint32_t p = 1;
   while (p < v) p <<= 1;
@@ -323,12 +339,17 @@ sweep_kernel(const SweepParams prm, const int o_w2, const int o_b2, const int o_
   };
   if (prm.n_stages == 1) load_stage(0);
   const float bo_sum = prm.hdr->bo_sum;
-  const float n_members_f = (float)prm.n_members;
+  // the weight stage doubles as sort scratch during pool compaction
+  unsigned long long* lds_keys = reinterpret_cast<unsigned long long*>(wts);
+  const uint32_t lds_entries = (uint32_t)prm.members_per_stage * (uint32_t)prm.member_floats / 2u;
+  // thread 0 keeps one chunk index in flight so the queue's latency is hidden
+  uint32_t next_chunk = 0;
+  if (tid == 0) next_chunk = atomicAdd(&prm.hdr->work_counter, 1u);
 
   for (;;) {
     __syncthreads();
     if (tid == 0) {
-      s_chunk = atomicAdd(&prm.hdr->work_counter, 1u);
+      s_chunk = next_chunk;
       if (prm.mode == MODE_TOPK) {
         const unsigned long long g =
             __hip_atomic_load(&prm.hdr->tau, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -339,13 +360,15 @@ sweep_kernel(const SweepParams prm, const int o_w2, const int o_b2, const int o_
     __syncthreads();
     const uint32_t chunk = s_chunk;
     if (chunk >= prm.n_chunks) break;
+    if (tid == 0) next_chunk = atomicAdd(&prm.hdr->work_counter, 1u);
 
     if (prm.mode == MODE_TOPK && s_compact) {
       const uint32_t n = s_cnt;
       const uint32_t n2 = next_pow2(n);
       for (uint32_t x = n + tid; x < n2; x += kThreads) pool[x] = kKeyMax;
       __syncthreads();
-      bitonic_sort(pool, n2, tid);
+      sort_pool(pool, n2, lds_keys, lds_entries, tid);
+      if (prm.n_stages == 1 && n2 <= lds_entries) load_stage(0);   // scratch held the weights
       if (tid == 0) {
         if (n >= (uint32_t)prm.k) {
           const unsigned long long t = pool[prm.k - 1];
@@ -372,14 +395,6 @@ sweep_kernel(const SweepParams prm, const int o_w2, const int o_b2, const int o_
       pos[r] = p0;
       const uint32_t i = (uint32_t)(prm.begin + (in_range ? p0 : prm.count - 1));
       idx[r] = i;
-#pragma unroll
-      for (int s = 0; s < KS1; ++s) {
-        const int p = 2 * s + h;
-        float f = 0.0f;
-        if (p < sp.n_params) f = feature_of(sp, p, digit_of(sp, p, i));
-        else if (p == sp.n_params) f = 1.0f;
-        xb[r][s] = f;
-      }
       bool v = in_range;
       for (int cc = 0; cc < sp.n_constraints; ++cc) {
         int ps = rule_partial_sum(sp, cc, i, h, 2);
@@ -389,6 +404,19 @@ sweep_kernel(const SweepParams prm, const int o_w2, const int o_b2, const int o_
       ok[r] = v;
       any[r] = __ballot(v) != 0ull;
       ysum[r] = 0.0f;
+      if (any[r]) {
+#pragma unroll
+        for (int s = 0; s < KS1; ++s) {
+          const int p = 2 * s + h;
+          float f = 0.0f;
+          if (p < sp.n_params) f = feature_of(sp, p, digit_of(sp, p, i));
+          else if (p == sp.n_params) f = 1.0f;
+          xb[r][s] = f;
+        }
+      } else {
+#pragma unroll
+        for (int s = 0; s < KS1; ++s) xb[r][s] = 0.0f;
+      }
     }
 
     // ---- ensemble
@@ -414,7 +442,7 @@ sweep_kernel(const SweepParams prm, const int o_w2, const int o_b2, const int o_
 #pragma unroll
     for (int r = 0; r < R; ++r) {
       float y = ysum[r] + __shfl_xor(ysum[r], 32);
-      y = (y + bo_sum) / n_members_f + 0.0f;
+      y = (y + bo_sum) * prm.inv_members + 0.0f;
       if (prm.mode == MODE_ALL) {
         if (h == 0 && pos[r] < prm.count) {
           prm.pred[pos[r]] = ok[r] ? y : __builtin_inff();
@@ -442,8 +470,7 @@ sweep_kernel(const SweepParams prm, const int o_w2, const int o_b2, const int o_
     n2 = n2 < prm.kp ? prm.kp : n2;
     for (uint32_t x = n + tid; x < n2; x += kThreads) pool[x] = kKeyMax;
     __syncthreads();
-    bitonic_sort(pool, n2, tid);
-    if (tid == 0 && n >= (uint32_t)prm.k) atomicMin(&prm.hdr->tau, pool[prm.k - 1]);
+    sort_pool(pool, n2, lds_keys, lds_entries, tid);
   }
 }
 
@@ -527,7 +554,7 @@ struct Layout {
 
 static uint32_t host_next_pow2(uint32_t v) { uint32_t p = 1; while (p < v) p <<= 1; return p; }
 
-constexpr int kMaxIter = kWaves * 4 * 32;   // largest chunk over the instantiated R
+constexpr int kMaxIter = kWaves * 2 * 32;   // largest chunk over the instantiated R
 
 static Layout make_layout(const Shape& sh, int k) {
   Layout L{};
@@ -548,12 +575,12 @@ struct Variant { int KS1, NT1, NT2, R; SweepFn fn; };
 
 #define TUNER_VARIANT(KS1, NT1, NT2, R) {KS1, NT1, NT2, R, sweep_kernel<KS1, NT1, NT2, R>}
 static const Variant kVariants[] = {
-    TUNER_VARIANT(4, 1, 0, 4),  TUNER_VARIANT(8, 1, 0, 4),  TUNER_VARIANT(12, 1, 0, 4), TUNER_VARIANT(16, 1, 0, 4),
-    TUNER_VARIANT(4, 2, 0, 4),  TUNER_VARIANT(8, 2, 0, 4),  TUNER_VARIANT(12, 2, 0, 4), TUNER_VARIANT(16, 2, 0, 4),
-    TUNER_VARIANT(4, 4, 0, 4),  TUNER_VARIANT(8, 4, 0, 4),  TUNER_VARIANT(12, 4, 0, 4), TUNER_VARIANT(16, 4, 0, 4),
-    TUNER_VARIANT(4, 1, 1, 4),  TUNER_VARIANT(8, 1, 1, 4),  TUNER_VARIANT(12, 1, 1, 4), TUNER_VARIANT(16, 1, 1, 4),
-    TUNER_VARIANT(4, 2, 2, 4),  TUNER_VARIANT(8, 2, 2, 4),  TUNER_VARIANT(12, 2, 2, 4), TUNER_VARIANT(16, 2, 2, 4),
-    TUNER_VARIANT(4, 4, 4, 2),  TUNER_VARIANT(8, 4, 4, 2),  TUNER_VARIANT(12, 4, 4, 2), TUNER_VARIANT(16, 4, 4, 2),
+    TUNER_VARIANT(4, 1, 0, 2),  TUNER_VARIANT(8, 1, 0, 2),  TUNER_VARIANT(12, 1, 0, 2), TUNER_VARIANT(16, 1, 0, 2),
+    TUNER_VARIANT(4, 2, 0, 2),  TUNER_VARIANT(8, 2, 0, 2),  TUNER_VARIANT(12, 2, 0, 2), TUNER_VARIANT(16, 2, 0, 2),
+    TUNER_VARIANT(4, 4, 0, 2),  TUNER_VARIANT(8, 4, 0, 2),  TUNER_VARIANT(12, 4, 0, 2), TUNER_VARIANT(16, 4, 0, 2),
+    TUNER_VARIANT(4, 1, 1, 2),  TUNER_VARIANT(8, 1, 1, 2),  TUNER_VARIANT(12, 1, 1, 2), TUNER_VARIANT(16, 1, 1, 2),
+    TUNER_VARIANT(4, 2, 2, 2),  TUNER_VARIANT(8, 2, 2, 2),  TUNER_VARIANT(12, 2, 2, 2), TUNER_VARIANT(16, 2, 2, 2),
+    TUNER_VARIANT(4, 4, 4, 1),  TUNER_VARIANT(8, 4, 4, 1),  TUNER_VARIANT(12, 4, 4, 1), TUNER_VARIANT(16, 4, 4, 1),
 };
 
 static const Variant* find_variant(Shape* sh) {
@@ -657,6 +684,7 @@ static int run_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin
     sw.n_stages = (sh.E + mps - 1) / mps;
     sw.member_floats = sh.member_floats;
     sw.mode = mode;
+    sw.inv_members = (float)(1.0 / (double)sh.E);
     sw.k = k;
     sw.cap = L.cap;
     sw.kp = L.kp;
