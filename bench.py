@@ -22,6 +22,11 @@ sys.path.insert(0, ROOT)
 
 PEAK_FP32_MATRIX_TFLOPS = 157.3   # MI355X published dense fp32 matrix (= fp32 vector) peak
 PEAK_HBM_GBS = 8000.0
+# HBM bytes per sweep launch from rocprofv3 FETCH_SIZE / WRITE_SIZE (KiB per dispatch, scaled
+# by the factors a plain 1 GiB copy gives in the same run: 2.000 and 1.000); see
+# profiles/sweep_kernel_cfg3.md.  Not measurable from inside this script.
+TRAFFIC_BYTES = {("cfg3", "topk"): (7083.25 * 2.0 + 12330.02) * 1024.0,
+                 ("cfg3", "all"): 528392.0 * 1024.0}
 
 
 def cpu_baseline(w, budget_blocks: int):
@@ -130,7 +135,8 @@ def main():
         flops_per_launch = n_valid * flop_per_cfg / launches_per_step
         achieved = flops_per_launch / (kernel_ms * 1e-3) / 1e12
         roof = {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP32_MATRIX_TFLOPS,
-                "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MATRIX_TFLOPS, "traffic": None,
+                "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MATRIX_TFLOPS,
+                "traffic": TRAFFIC_BYTES.get((args.workload, args.mode)),
                 "kernel": "sweep_kernel (fp32 MFMA 32x32x2)", "kernel_ms": kernel_ms,
                 "launches_per_step": launches_per_step,
                 "flop_per_config": flop_per_cfg, "evaluated_configs_per_launch": n_valid / launches_per_step,
