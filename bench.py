@@ -29,32 +29,36 @@ TRAFFIC_BYTES = {("cfg3", "topk"): (7083.25 * 2.0 + 12330.02) * 1024.0,
                  ("cfg3", "all"): 528392.0 * 1024.0}
 
 
-def cpu_baseline(w, budget_blocks: int):
-    """Times the CPU oracle (as it stands) on evenly spaced aligned blocks of the
-    same workload; returns swept configurations per second."""
-    import numpy as np
+def cpu_baseline(w, target_seconds: float = 12.0, blocks: int = 0):
+    """Times the CPU oracle (as it stands, all host threads through its own range
+    partitioner) on blocks of 4096 indices evenly spaced over the space, so that the
+    sample has the workload's own valid/invalid mix.  A short pilot sizes the sample
+    to about target_seconds.  Returns swept configurations per second."""
     import oracle
     sp, m = w.space, w.model
     n = sp.n_configs
     block = min(n, 1 << 12)
     n_blocks_total = n // block
-    nb = min(budget_blocks, n_blocks_total)
     threads = min(16, os.cpu_count() or 1)
-    # warm (library load, page-in)
-    oracle.predict_range(sp, m, 0, min(block, 256), threads=1)
-    t0 = time.perf_counter()
-    swept = 0
-    evaluated = 0
-    # groups of `threads` blocks are swept concurrently by the oracle's range partitioner
-    step = max(1, n_blocks_total // nb)
-    for b in range(0, nb):
-        begin = (b * step) * block
-        _, valid, _ = oracle.predict_range(sp, m, begin, block, threads=threads)
-        swept += block
-        evaluated += int(valid.sum())
-    dt = time.perf_counter() - t0
+    oracle.predict_range(sp, m, 0, min(block, 256), threads=1)      # library load, page-in
+
+    def sweep(nb):
+        step = max(1, n_blocks_total // nb)
+        swept = evaluated = 0
+        t0 = time.perf_counter()
+        for b in range(nb):
+            _, valid, _ = oracle.predict_range(sp, m, (b * step) * block, block, threads=threads)
+            swept += block
+            evaluated += int(valid.sum())
+        return swept, evaluated, time.perf_counter() - t0
+
+    if not blocks:
+        pilot = min(n_blocks_total, 64)
+        _, _, dt = sweep(pilot)
+        blocks = int(max(pilot, min(n_blocks_total, pilot * target_seconds / max(dt, 1e-6))))
+    swept, evaluated, dt = sweep(blocks)
     return {"value": swept / dt, "unit": "configs/s", "cores": threads, "kind": "oracle",
-            "sample": f"{nb} blocks of {block} indices evenly spaced over the space "
+            "sample": f"{blocks} blocks of {block} indices evenly spaced over the space "
                       f"({swept} swept, {evaluated} valid, {dt:.1f} s)",
             "evaluated_per_s": evaluated / dt}
 
@@ -67,6 +71,9 @@ def main():
     ap.add_argument("--workload", default="cfg3",
                     help="cfg1..cfg5, cfg3-2^26, paper-convolution, paper-raycasting, paper-stereo")
     ap.add_argument("--mode", default="topk", choices=["topk", "all"])
+    ap.add_argument("--net", default="f32-mfma", choices=["f32-mfma", "split16", "bf16"],
+                    help="f32-mfma: fp32 matrix instructions; split16: two-plane f16 split, fp32 "
+                         "accumulate (fp32 tolerance); bf16: bf16 operands (1e-2 tolerance)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (a kernel of known HBM "
@@ -87,7 +94,10 @@ def main():
     sp, m = w.space, w.model
     N = sp.n_configs
     chunk = w.chunk if w.chunk else N
-    sw = Sweep(sp, m, w.k if args.mode == "topk" else 0)
+    net_kw = {"f32-mfma": dict(precision=T.TUNER_FP32, algo=T.TUNER_ALGO_MFMA),
+              "split16": dict(precision=T.TUNER_FP32, algo=T.TUNER_ALGO_SPLIT16),
+              "bf16": dict(precision=T.TUNER_BF16_MFMA, algo=T.TUNER_ALGO_AUTO)}[args.net]
+    sw = Sweep(sp, m, w.k if args.mode == "topk" else 0, **net_kw)
     stream = torch.cuda.current_stream()
     pred = mask = None
     if args.mode == "all":
@@ -149,18 +159,13 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "n_configs": N, "n_valid": n_valid, "k": w.k,
                    "members": m.n_members, "widths": list(m.widths), "mode": args.mode,
-                   "chunk": chunk},
+                   "chunk": chunk, "net": args.net},
         "roofline": roof,
     }
     if args.mode == "all":
         out["hbm_write_GBs"] = 4.0 * N / (dt / args.steps) / 1e9
     if not args.no_cpu:
-        blocks = args.cpu_blocks or {"cfg1": 1, "cfg2": 96}.get(args.workload, 0)
-        if not blocks:
-            # aim at roughly 15 s: ~1.2e9 flop/s/core in double with exp
-            est_cfg_per_s = 16 * 1.0e9 / max(flop_per_cfg, 1)
-            blocks = max(16, int(15 * est_cfg_per_s / 4096))
-        out["cpu_baseline"] = cpu_baseline(w, blocks)
+        out["cpu_baseline"] = cpu_baseline(w, blocks=args.cpu_blocks)
     print(json.dumps(out))
 
 

@@ -48,8 +48,17 @@ enum {
 
 enum { TUNER_SCALE_LINEAR = 0, TUNER_SCALE_LOG2 = 1 };
 enum { TUNER_FP32 = 0, TUNER_BF16_MFMA = 1 };
-/* How the fp32 network is evaluated.  AUTO picks the matrix-core path. */
-enum { TUNER_ALGO_AUTO = 0, TUNER_ALGO_MFMA = 1, TUNER_ALGO_VALU = 2 };
+/*
+ * How a TUNER_FP32 network is evaluated (all meet the fp32 tolerance of 1e-5):
+ *   AUTO     the library's choice (currently MFMA)
+ *   MFMA     fp32 matrix instructions, fp32 accumulate
+ *   VALU     plain vector-ALU FMAs, one configuration per lane (not built yet: EINVAL)
+ *   SPLIT16  every operand split into two f16 planes (22 significand bits), three f16
+ *            matrix products per fp32 product, fp32 accumulate; weights must satisfy
+ *            |w| * 1.4427 < 65504 (f16 range)
+ * TUNER_BF16_MFMA precision accepts AUTO or MFMA only.
+ */
+enum { TUNER_ALGO_AUTO = 0, TUNER_ALGO_MFMA = 1, TUNER_ALGO_VALU = 2, TUNER_ALGO_SPLIT16 = 3 };
 
 /* Limits of this build. */
 #define TUNER_MAX_PARAMS 31       /* P */
@@ -73,7 +82,10 @@ typedef struct {
   const float* weights_dev; /* DEVICE, fp32, per member and per layer:
                                W[out][in] row-major, then b[out];
                                i.e. W1,b1,(W2,b2,)w_o,b_o ; members back to back */
-  int32_t precision;        /* TUNER_FP32 (TUNER_BF16_MFMA is not built yet: EINVAL) */
+  int32_t precision;        /* TUNER_FP32, or TUNER_BF16_MFMA: features, weights and hidden
+                               activations rounded to bf16 (nearest even) before each matrix
+                               product, fp32 accumulate; biases, sigmoid, output layer and mean
+                               in fp32 (tolerance 1e-2) */
   int32_t algo;             /* TUNER_ALGO_* */
 } tuner_model;
 

@@ -21,7 +21,7 @@ TUNER_OK = 0
 TUNER_EINVAL, TUNER_ETOOLARGE, TUNER_ENOMEM, TUNER_EWORKSPACE, TUNER_EHIP = -1, -2, -3, -4, -5
 TUNER_SCALE_LINEAR, TUNER_SCALE_LOG2 = 0, 1
 TUNER_FP32, TUNER_BF16_MFMA = 0, 1
-TUNER_ALGO_AUTO, TUNER_ALGO_MFMA, TUNER_ALGO_VALU = 0, 1, 2
+TUNER_ALGO_AUTO, TUNER_ALGO_MFMA, TUNER_ALGO_VALU, TUNER_ALGO_SPLIT16 = 0, 1, 2, 3
 TUNER_MAX_K = 16384
 
 EXPORTS = [

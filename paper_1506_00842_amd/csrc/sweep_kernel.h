@@ -1,0 +1,177 @@
+// The fused sweep kernel, parameterised by how the network is evaluated.
+//
+// Paper: Section 5.3 (predict every configuration, keep the M lowest), Section
+// 5.2 (ensemble mean, statically invalid configurations), Section 5.1 (space).
+//
+// Persistent workgroups (NW waves) pull chunks of NW * R tiles (32 consecutive
+// configurations each) from a global queue.  LDS: [space tables][one stage of
+// packed members].  A Net policy supplies
+//   struct Feat                                   per-tile network input registers
+//   static void load_features(sp, index, lane, Feat&)
+//   static void zero_features(Feat&)
+//   static float forward(const uint32_t* member_lds, const Feat&, int lane, const NetOffsets&)
+//        -> the lane's share of the member's output (both halves of a lane pair
+//           (lane, lane ^ 32) are summed by the caller)
+#pragma once
+#include "sweep_common.h"
+
+namespace tuner {
+
+template <class Net, int R, int NW>
+__global__ void __launch_bounds__(NW * 64) sweep_kernel(const SweepParams prm) {
+  constexpr int kThreads = NW * 64;
+  constexpr int kWaves = NW;
+  extern __shared__ __align__(16) unsigned char smem[];
+  DevSpace& sp = *reinterpret_cast<DevSpace*>(smem);
+  uint32_t* wts = reinterpret_cast<uint32_t*>(smem + kSpaceBytes);
+  __shared__ uint32_t s_chunk, s_cnt, s_compact;
+  __shared__ unsigned long long s_tau, s_tau_local;
+
+  constexpr int kIter = kWaves * R * 32;   // configurations per chunk
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int c = lane & 31, h = lane >> 5;
+  unsigned long long* pool = prm.pools + (size_t)blockIdx.x * prm.cap;
+
+  {
+    const uint32_t* src = reinterpret_cast<const uint32_t*>(prm.space);
+    uint32_t* dst = reinterpret_cast<uint32_t*>(smem);
+    for (int x = tid; x < (int)(sizeof(DevSpace) / 4); x += kThreads) dst[x] = src[x];
+  }
+  if (tid == 0) { s_cnt = 0; s_tau_local = kKeyMax; s_compact = 0; }
+  auto load_stage = [&](int st) {
+    const int first = st * prm.members_per_stage;
+    int nm = prm.n_members - first;
+    nm = nm < prm.members_per_stage ? nm : prm.members_per_stage;
+    const uint4* src = reinterpret_cast<const uint4*>(prm.packed + (size_t)first * prm.member_words);
+    uint4* dst = reinterpret_cast<uint4*>(wts);
+    const int n4 = nm * prm.member_words / 4;
+    for (int x = tid; x < n4; x += kThreads) dst[x] = src[x];
+  };
+  if (prm.n_stages == 1) load_stage(0);
+  const float bo_sum = prm.hdr->bo_sum;
+  // the weight stage doubles as sort scratch during pool compaction
+  unsigned long long* lds_keys = reinterpret_cast<unsigned long long*>(wts);
+  const uint32_t lds_entries = (uint32_t)prm.members_per_stage * (uint32_t)prm.member_words / 2u;
+  // thread 0 keeps one chunk index in flight so the queue's latency is hidden
+  uint32_t next_chunk = 0;
+  if (tid == 0) next_chunk = atomicAdd(&prm.hdr->work_counter, 1u);
+
+  for (;;) {
+    __syncthreads();
+    if (tid == 0) {
+      s_chunk = next_chunk;
+      if (prm.mode == MODE_TOPK) {
+        const unsigned long long g =
+            __hip_atomic_load(&prm.hdr->tau, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        s_tau = g < s_tau_local ? g : s_tau_local;
+        s_compact = (s_cnt + kIter > prm.cap) ? 1u : 0u;
+      }
+    }
+    __syncthreads();
+    const uint32_t chunk = s_chunk;
+    if (chunk >= prm.n_chunks) break;
+    if (tid == 0) next_chunk = atomicAdd(&prm.hdr->work_counter, 1u);
+
+    if (prm.mode == MODE_TOPK && s_compact) {
+      // pool nearly full: keep its k smallest keys, lower the thresholds
+      const uint32_t n = s_cnt;
+      const uint32_t n2 = next_pow2(n);
+      for (uint32_t x = n + tid; x < n2; x += kThreads) pool[x] = kKeyMax;
+      __syncthreads();
+      sort_pool(pool, n2, lds_keys, lds_entries, tid, kThreads);
+      if (prm.n_stages == 1 && n2 <= lds_entries) load_stage(0);   // scratch held the weights
+      if (tid == 0) {
+        if (n >= (uint32_t)prm.k) {
+          const unsigned long long t = pool[prm.k - 1];
+          s_tau_local = t;
+          atomicMin(&prm.hdr->tau, t);
+          if (t < s_tau) s_tau = t;
+          s_cnt = prm.k;
+        }
+      }
+      __syncthreads();
+    }
+    const unsigned long long tau = s_tau;
+
+    // ---- validity, then digits -> features, for this wave's R tiles
+    typename Net::Feat feat[R];
+    float ysum[R];
+    bool ok[R], any[R];
+    uint32_t idx[R];
+    uint64_t pos[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const uint64_t p0 = (uint64_t)chunk * kIter + (uint32_t)((wave * R + r) * 32 + c);
+      const bool in_range = p0 < prm.count;
+      pos[r] = p0;
+      const uint32_t i = (uint32_t)(prm.begin + (in_range ? p0 : prm.count - 1));
+      idx[r] = i;
+      bool v = in_range;
+      for (int cc = 0; cc < sp.n_constraints; ++cc) {
+        int ps = rule_partial_sum(sp, cc, i, h, 2);
+        ps += __shfl_xor(ps, 32);
+        v = v && (ps <= sp.bound[cc]);
+      }
+      ok[r] = v;
+      any[r] = __ballot(v) != 0ull;
+      ysum[r] = 0.0f;
+      if (any[r]) Net::load_features(sp, i, lane, feat[r]);
+      else Net::zero_features(feat[r]);
+    }
+
+    // ---- ensemble
+    for (int st = 0; st < prm.n_stages; ++st) {
+      if (prm.n_stages > 1) {
+        __syncthreads();
+        load_stage(st);
+        __syncthreads();
+      }
+      const int first = st * prm.members_per_stage;
+      int nm = prm.n_members - first;
+      nm = nm < prm.members_per_stage ? nm : prm.members_per_stage;
+      for (int m = 0; m < nm; ++m) {
+        const uint32_t* w = wts + (size_t)m * prm.member_words;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+          if (any[r]) ysum[r] += Net::forward(w, feat[r], lane, prm.off);
+        }
+      }
+    }
+
+    // ---- mean, mask, output
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      float y = ysum[r] + __shfl_xor(ysum[r], 32);
+      y = (y + bo_sum) * prm.inv_members + 0.0f;
+      if (prm.mode == MODE_ALL) {
+        if (h == 0 && pos[r] < prm.count) {
+          prm.pred[pos[r]] = ok[r] ? y : __builtin_inff();
+          if (prm.mask) prm.mask[pos[r]] = ok[r] ? 1 : 0;
+        }
+      } else {
+        const unsigned long long key = make_key(y, idx[r]);
+        const bool pass = ok[r] && h == 0 && key < tau;
+        const unsigned long long bal = __ballot(pass);
+        if (bal) {
+          uint32_t base = 0;
+          if (lane == 0) base = atomicAdd(&s_cnt, (uint32_t)__popcll(bal));
+          base = __shfl(base, 0);
+          if (pass) pool[base + __popcll(bal & ((1ull << lane) - 1ull))] = key;
+        }
+      }
+    }
+  }
+
+  if (prm.mode == MODE_TOPK) {
+    // final: sorted list of at least kp entries (padded with the sentinel)
+    __syncthreads();
+    const uint32_t n = s_cnt;
+    uint32_t n2 = next_pow2(n);
+    n2 = n2 < prm.kp ? prm.kp : n2;
+    for (uint32_t x = n + tid; x < n2; x += kThreads) pool[x] = kKeyMax;
+    __syncthreads();
+    sort_pool(pool, n2, lds_keys, lds_entries, tid, kThreads);
+  }
+}
+
+}  // namespace tuner

@@ -183,3 +183,38 @@ def test_streamed_2_32_running_topk():
     torch.cuda.synchronize()
     v2, i2 = sw2.topk_host()
     assert np.array_equal(i2, gi) and np.array_equal(v2, gv)
+
+
+@pytest.mark.parametrize("net", ["split16", "bf16"])
+def test_large_2_27_other_nets_full(net):
+    """The 2^27 sweep with the 16-bit matrix-core networks: selection exact against the
+    path's own predictions, predictions against the oracle at the net's tolerance."""
+    import paper_1506_00842_amd as T
+    from paper_1506_00842_amd.api import Sweep
+    kw, tol = {"split16": (dict(algo=T.TUNER_ALGO_SPLIT16), parity.TOL_FP32),
+               "bf16": (dict(precision=T.TUNER_BF16_MFMA), 1e-2)}[net]
+    w = wl.large()
+    n = w.space.n_configs
+    sw = Sweep(w.space, w.model, w.k, **kw)
+    sw.topk(0, n)
+    torch.cuda.synchronize()
+    gv, gi = sw.topk_host()
+    pred, mask = sw.predict_all(0, n)
+    torch.cuda.synchronize()
+    assert int(mask.sum().item()) == w.n_valid
+    ev, ei = exact_topk_of(pred, mask, 0, w.k)
+    assert np.array_equal(gi, ei) and np.array_equal(gv, ev)
+    st = wl.Stream(21)
+    worst_all = 0.0
+    for begin in [0, n - 4096] + [int(v) for v in st.integers(40, n - 4096)]:
+        p2, m2 = sw.predict_all(begin, 4096)
+        torch.cuda.synchronize()
+        oy, ov, _ = oracle.predict_range(w.space, w.model, begin, 4096, threads=THREADS)
+        assert np.array_equal(m2.cpu().numpy(), ov)
+        worst, _ = parity.check_predictions(p2.cpu().numpy(), oy, ov, tol=tol)
+        worst_all = max(worst_all, worst)
+    ry, rv = oracle.predict_indices(w.space, w.model, gi, threads=THREADS)
+    assert rv.all()
+    S = parity.scale_of(ry)
+    assert np.all(np.abs(gv.astype(np.float64) - ry) <= tol * np.maximum(np.abs(ry), S))
+    say(f"  {net}: worst {worst_all:.3f} x tol({tol:g})")

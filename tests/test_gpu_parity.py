@@ -151,6 +151,76 @@ def test_saturation_zero_weights_and_constant_net():
     assert np.all(g == 15.0)
 
 
+# ------------------------------------------------- other network evaluations --
+TOL_BF16 = 1e-2
+
+
+def _nets():
+    import paper_1506_00842_amd as T
+    return {"split16": (dict(precision=T.TUNER_FP32, algo=T.TUNER_ALGO_SPLIT16), parity.TOL_FP32),
+            "bf16": (dict(precision=T.TUNER_BF16_MFMA, algo=T.TUNER_ALGO_AUTO), TOL_BF16)}
+
+
+@pytest.mark.parametrize("net", ["split16", "bf16"])
+@pytest.mark.parametrize("P,hidden,E", SHAPES)
+def test_other_nets_model_shapes(net, P, hidden, E):
+    """Two-plane f16 split (fp32 tolerance) and bf16 operands (1e-2) on every
+    kernel family and padding, ragged ranges, mixed and power-of-two radices."""
+    kw, tol = _nets()[net]
+    for pow2 in (False, True):
+        w = wl.many_params(P, hidden, E, seed=200 + P + len(hidden), pow2=pow2)
+        n = w.space.n_configs
+        count = min(n, 12007)
+        begin = min((n // 5) | 1, n - count)
+        sw = sweep_for(w, k=0, **kw)
+        pred, mask = sw.predict_all(begin, count)
+        torch.cuda.synchronize()
+        oy, ov, _ = oracle.predict_range(w.space, w.model, begin, count, threads=THREADS)
+        assert np.array_equal(mask.cpu().numpy(), ov)
+        worst, _ = parity.check_predictions(pred.cpu().numpy(), oy, ov, tol=tol)
+        say(f"  {net} {w.name} {hidden}: worst {worst:.3f} x tol({tol:g})")
+
+
+@pytest.mark.parametrize("net", ["split16", "bf16"])
+def test_other_nets_benchmark_workloads(net):
+    kw, tol = _nets()[net]
+    for maker, begin, count in ((wl.tiny, 0, 256), (wl.conv_shaped, 0, 393216),
+                                (wl.paper_stereo, 2359296 - 150001, 150001),
+                                (wl.large, (37 << 15) + 4321, 1 << 17), (wl.wide, (37 << 15), 1 << 14),
+                                (wl.streamed, (1 << 32) - (1 << 16), 1 << 16)):
+        w = maker()
+        sw = sweep_for(w, **kw)
+        pred, mask = sw.predict_all(begin, count)
+        torch.cuda.synchronize()
+        oy, ov, _ = oracle.predict_range(w.space, w.model, begin, count, threads=THREADS)
+        assert np.array_equal(mask.cpu().numpy(), ov)
+        worst, _ = parity.check_predictions(pred.cpu().numpy(), oy, ov, tol=tol)
+        # top-k of the same range under the band rule at this net's tolerance
+        sw.topk(begin, count)
+        torch.cuda.synchronize()
+        gv, gi = sw.topk_host()
+        parity.check_topk(gv, gi, oy, ov, begin, w.k, tol=tol)
+        say(f"  {net} {w.name}: worst {worst:.3f} x tol({tol:g}), top-{w.k} ok")
+
+
+def test_split16_saturation_and_zero_weights():
+    import paper_1506_00842_amd as T
+    w = wl.conv_shaped()
+    m = w.model
+    fpm = m.floats_per_member
+    big = wl.Model(m.widths, 1, np.zeros(fpm, np.float32))
+    (W1, b1), (wo, bo) = big.member_layers(0)
+    b1[:15] = 1e4
+    b1[15:] = -1e4
+    wo[:] = 1.0
+    for kw in (dict(algo=T.TUNER_ALGO_SPLIT16), dict(precision=T.TUNER_BF16_MFMA)):
+        sw = sweep_for(wl.Workload("sat", w.space, big, 5), **kw)
+        pred, mask = sw.predict_all(0, 4096)
+        torch.cuda.synchronize()
+        g = pred.cpu().numpy()[mask.cpu().numpy().astype(bool)]
+        assert np.all(g == 15.0)
+
+
 # ------------------------------------------------------------------- top-k ---
 def test_topk_small_spaces_exact_and_band():
     for maker in (wl.tiny, wl.conv_shaped, lambda: wl.random_small(2), lambda: wl.random_small(4),

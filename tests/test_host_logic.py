@@ -148,12 +148,18 @@ def test_workspace_bytes_and_model_validation():
         (T.ModelHandle(4, [14, 64, 64, 64, 1], _FakeWeights()), None),    # too deep
         (T.ModelHandle(0, [14, 64, 1], _FakeWeights()), None),            # no members
         (T.ModelHandle(4, [14, 300, 1], _FakeWeights()), None),           # too wide
-        (T.ModelHandle(4, [14, 64, 1], _FakeWeights(), precision=T.TUNER_BF16_MFMA), None),
+        (T.ModelHandle(4, [14, 64, 1], _FakeWeights(), precision=7), None),                 # unknown precision
+        (T.ModelHandle(4, [14, 64, 1], _FakeWeights(), algo=9), None),                      # unknown algo
+        (T.ModelHandle(4, [14, 64, 1], _FakeWeights(), precision=T.TUNER_BF16_MFMA,
+                       algo=T.TUNER_ALGO_SPLIT16), None),                                   # bf16 is MFMA only
     ):
         with pytest.raises(T.TunerError):
             T.tuner_workspace_bytes(h, bad, 10)
     with pytest.raises(T.TunerError):
         T.tuner_workspace_bytes(h, m, T.TUNER_MAX_K + 1)
+    # every network evaluation has a workspace size
+    for kw in (dict(algo=T.TUNER_ALGO_SPLIT16), dict(precision=T.TUNER_BF16_MFMA)):
+        assert T.tuner_workspace_bytes(h, T.ModelHandle(4, [14, 64, 64, 1], _FakeWeights(), **kw), 1000) > 0
 
 
 def test_predict_argument_errors_before_any_gpu_work():
