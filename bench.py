@@ -71,10 +71,12 @@ def main():
     ap.add_argument("--workload", default="cfg3",
                     help="cfg1..cfg5, cfg3-2^26, paper-convolution, paper-raycasting, paper-stereo")
     ap.add_argument("--mode", default="topk", choices=["topk", "all"])
-    ap.add_argument("--net", default="f32-mfma", choices=["f32-mfma", "split16", "bf16"],
+    ap.add_argument("--net", default="f32-mfma", choices=["f32-mfma", "split16", "bf16", "valu"],
                     help="f32-mfma: fp32 matrix instructions; split16: two-plane f16 split, fp32 "
                          "accumulate (fp32 tolerance); bf16: bf16 operands (1e-2 tolerance)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--no-other-nets", action="store_true",
+                    help="skip the short untimed-region comparison runs of the other network evaluations")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (a kernel of known HBM "
                          "traffic, to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -96,6 +98,7 @@ def main():
     chunk = w.chunk if w.chunk else N
     net_kw = {"f32-mfma": dict(precision=T.TUNER_FP32, algo=T.TUNER_ALGO_MFMA),
               "split16": dict(precision=T.TUNER_FP32, algo=T.TUNER_ALGO_SPLIT16),
+              "valu": dict(precision=T.TUNER_FP32, algo=T.TUNER_ALGO_VALU),
               "bf16": dict(precision=T.TUNER_BF16_MFMA, algo=T.TUNER_ALGO_AUTO)}[args.net]
     sw = Sweep(sp, m, w.k if args.mode == "topk" else 0, **net_kw)
     stream = torch.cuda.current_stream()
@@ -162,6 +165,32 @@ def main():
                    "chunk": chunk, "net": args.net},
         "roofline": roof,
     }
+    if not args.no_other_nets and args.mode == "topk":
+        # the same workload with the other network evaluations (3 steps each, outside the
+        # timed region above): context for the choice of the matrix-core path
+        others = {}
+        for name, kw in (("f32-mfma", dict(algo=T.TUNER_ALGO_MFMA)), ("split16", dict(algo=T.TUNER_ALGO_SPLIT16)),
+                         ("valu", dict(algo=T.TUNER_ALGO_VALU)), ("bf16", dict(precision=T.TUNER_BF16_MFMA))):
+            if name == args.net:
+                continue
+            sw2 = Sweep(sp, m, w.k, **kw)
+
+            def step2():
+                first = True
+                for b in range(0, N, chunk):
+                    sw2.topk(b, min(chunk, N - b), merge=not first, stream=stream)
+                    first = False
+            step2()
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            for _ in range(3):
+                step2()
+            torch.cuda.synchronize()
+            d2 = (time.perf_counter() - t1) / 3
+            others[name] = {"ms_per_step": 1e3 * d2, "configs_per_s": N / d2,
+                            "tolerance": 1e-2 if name == "bf16" else 1e-5}
+            del sw2
+        out["other_nets"] = others
     if args.mode == "all":
         out["hbm_write_GBs"] = 4.0 * N / (dt / args.steps) / 1e9
     if not args.no_cpu:

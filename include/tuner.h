@@ -52,7 +52,7 @@ enum { TUNER_FP32 = 0, TUNER_BF16_MFMA = 1 };
  * How a TUNER_FP32 network is evaluated (all meet the fp32 tolerance of 1e-5):
  *   AUTO     the library's choice (currently MFMA)
  *   MFMA     fp32 matrix instructions, fp32 accumulate
- *   VALU     plain vector-ALU FMAs, one configuration per lane (not built yet: EINVAL)
+ *   VALU     plain vector-ALU FMAs, one configuration per lane, weights broadcast from LDS
  *   SPLIT16  every operand split into two f16 planes (22 significand bits), three f16
  *            matrix products per fp32 product, fp32 accumulate; weights must satisfy
  *            |w| * 1.4427 < 65504 (f16 range)

@@ -26,6 +26,7 @@ namespace tuner {
 
 template <int KS1, int NT1, int NT2>
 struct F32Net {
+  static constexpr int kTile = 32;
   struct Feat { float x[KS1]; };   // B operand of layer 1: feature 2 s + h, 1.0 in the bias slot
 
   static __device__ __forceinline__ void load_features(const DevSpace& sp, uint32_t i, int lane, Feat& f) {

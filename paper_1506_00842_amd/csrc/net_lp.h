@@ -71,6 +71,7 @@ __device__ __forceinline__ void pack_pair(float a, float b, uint32_t& hi, uint32
 template <class T, int NPL, int KB1, int NT1, int NT2>
 struct LpNet {
   typedef LpTraits<T> Tr;
+  static constexpr int kTile = 32;
   struct Feat { B4 x[NPL][KB1]; };
 
   static __device__ __forceinline__ void load_features(const DevSpace& sp, uint32_t i, int lane, Feat& f) {

@@ -10,7 +10,7 @@ namespace tuner {
 
 constexpr int kMergeThreads = 1024;
 constexpr int kMaxGroups = 256;           // persistent workgroups (MI355X: 256 CUs)
-constexpr int kMaxIter = 1024;            // most configurations per chunk (waves * R * 32) over all variants
+constexpr int kMaxIter = 1024;            // most configurations per chunk (waves * R * tile) over all variants
 constexpr unsigned long long kKeyMax = ~0ull;
 constexpr int kSpaceBytes = (sizeof(DevSpace) + 255) / 256 * 256;
 constexpr float kNegLog2e = -1.44269504088896340736f;
@@ -40,7 +40,7 @@ struct Shape {
   int raw_member_floats;
 };
 
-struct NetOffsets { int w1, w2, b1, b2, wo; };
+struct NetOffsets { int w1, w2, b1, b2, wo, h1, h2; };   // word offsets; real hidden widths
 
 struct SweepParams {
   uint64_t begin, count;
@@ -59,12 +59,12 @@ struct SweepParams {
 };
 
 typedef void (*SweepFn)(const SweepParams);
-struct Variant { int net, KS, NT1, NT2, R, waves; SweepFn fn; };
+struct Variant { int net, KS, NT1, NT2, R, waves, tile; SweepFn fn; };
 
 // Lookups implemented next to the instantiations (one translation unit per family).
 const Variant* find_variant_f32(int KS, int NT1, int NT2);
 const Variant* find_variant_lp(int net, int KS, int NT1, int NT2);
-const Variant* find_variant_valu(int NT1, int NT2);
+const Variant* find_variant_valu(int KS, int NT1, int NT2);
 
 #if defined(__HIPCC__)
 __device__ __forceinline__ uint32_t order_bits(float y) {

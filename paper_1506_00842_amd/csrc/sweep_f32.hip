@@ -4,7 +4,7 @@
 
 namespace tuner {
 
-#define TUNER_F32(KS, NT1, NT2, R, NW) {NET_F32_MFMA, KS, NT1, NT2, R, NW, sweep_kernel<F32Net<KS, NT1, NT2>, R, NW>}
+#define TUNER_F32(KS, NT1, NT2, R, NW) {NET_F32_MFMA, KS, NT1, NT2, R, NW, 32, sweep_kernel<F32Net<KS, NT1, NT2>, R, NW>}
 static const Variant kF32Variants[] = {
     TUNER_F32(4, 1, 0, 2, 16),  TUNER_F32(8, 1, 0, 2, 16),  TUNER_F32(12, 1, 0, 2, 16), TUNER_F32(16, 1, 0, 2, 16),
     TUNER_F32(4, 2, 0, 2, 16),  TUNER_F32(8, 2, 0, 2, 16),  TUNER_F32(12, 2, 0, 2, 16), TUNER_F32(16, 2, 0, 2, 16),

@@ -6,6 +6,9 @@
 // Persistent workgroups (NW waves) pull chunks of NW * R tiles (32 consecutive
 // configurations each) from a global queue.  LDS: [space tables][one stage of
 // packed members].  A Net policy supplies
+//   static constexpr int kTile                    configurations per wave and tile: 32 (each
+//                                                 configuration is shared by the lane pair
+//                                                 (lane, lane ^ 32)) or 64 (one per lane)
 //   struct Feat                                   per-tile network input registers
 //   static void load_features(sp, index, lane, Feat&)
 //   static void zero_features(Feat&)
@@ -27,9 +30,10 @@ __global__ void __launch_bounds__(NW * 64) sweep_kernel(const SweepParams prm) {
   __shared__ uint32_t s_chunk, s_cnt, s_compact;
   __shared__ unsigned long long s_tau, s_tau_local;
 
-  constexpr int kIter = kWaves * R * 32;   // configurations per chunk
+  constexpr int kTile = Net::kTile;
+  constexpr int kIter = kWaves * R * kTile;   // configurations per chunk
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int c = lane & 31, h = lane >> 5;
+  const int c = kTile == 32 ? (lane & 31) : lane, h = kTile == 32 ? (lane >> 5) : 0;
   unsigned long long* pool = prm.pools + (size_t)blockIdx.x * prm.cap;
 
   {
@@ -101,15 +105,20 @@ __global__ void __launch_bounds__(NW * 64) sweep_kernel(const SweepParams prm) {
     uint64_t pos[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-      const uint64_t p0 = (uint64_t)chunk * kIter + (uint32_t)((wave * R + r) * 32 + c);
+      const uint64_t p0 = (uint64_t)chunk * kIter + (uint32_t)((wave * R + r) * kTile + c);
       const bool in_range = p0 < prm.count;
       pos[r] = p0;
       const uint32_t i = (uint32_t)(prm.begin + (in_range ? p0 : prm.count - 1));
       idx[r] = i;
       bool v = in_range;
       for (int cc = 0; cc < sp.n_constraints; ++cc) {
-        int ps = rule_partial_sum(sp, cc, i, h, 2);
-        ps += __shfl_xor(ps, 32);
+        int ps;
+        if constexpr (kTile == 32) {
+          ps = rule_partial_sum(sp, cc, i, h, 2);     // the lane pair splits the rule's entries
+          ps += __shfl_xor(ps, 32);
+        } else {
+          ps = rule_partial_sum(sp, cc, i, 0, 1);
+        }
         v = v && (ps <= sp.bound[cc]);
       }
       ok[r] = v;
@@ -141,7 +150,8 @@ __global__ void __launch_bounds__(NW * 64) sweep_kernel(const SweepParams prm) {
     // ---- mean, mask, output
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-      float y = ysum[r] + __shfl_xor(ysum[r], 32);
+      float y = ysum[r];
+      if constexpr (kTile == 32) y += __shfl_xor(y, 32);
       y = (y + bo_sum) * prm.inv_members + 0.0f;
       if (prm.mode == MODE_ALL) {
         if (h == 0 && pos[r] < prm.count) {

@@ -5,8 +5,8 @@
 
 namespace tuner {
 
-#define TUNER_BF16(KB, NT1, NT2, R, NW) {NET_BF16, KB, NT1, NT2, R, NW, sweep_kernel<LpNet<__bf16, 1, KB, NT1, NT2>, R, NW>}
-#define TUNER_F16X2(KB, NT1, NT2, R, NW) {NET_F16X2, KB, NT1, NT2, R, NW, sweep_kernel<LpNet<_Float16, 2, KB, NT1, NT2>, R, NW>}
+#define TUNER_BF16(KB, NT1, NT2, R, NW) {NET_BF16, KB, NT1, NT2, R, NW, 32, sweep_kernel<LpNet<__bf16, 1, KB, NT1, NT2>, R, NW>}
+#define TUNER_F16X2(KB, NT1, NT2, R, NW) {NET_F16X2, KB, NT1, NT2, R, NW, 32, sweep_kernel<LpNet<_Float16, 2, KB, NT1, NT2>, R, NW>}
 static const Variant kLpVariants[] = {
     TUNER_BF16(1, 1, 0, 2, 16), TUNER_BF16(2, 1, 0, 2, 16), TUNER_BF16(1, 2, 0, 2, 16), TUNER_BF16(2, 2, 0, 2, 16),
     TUNER_BF16(1, 4, 0, 2, 8), TUNER_BF16(2, 4, 0, 2, 8), TUNER_BF16(1, 1, 1, 2, 16), TUNER_BF16(2, 1, 1, 2, 16),

@@ -25,6 +25,7 @@
 
 #include "net_f32.h"
 #include "net_lp.h"
+#include "net_valu.h"
 #include "sweep_common.h"
 #include "tuner_internal.h"
 
@@ -61,6 +62,7 @@ __global__ void __launch_bounds__(256) prep_kernel(const DevSpace sp, const Prep
     uint32_t word;
     if (sh.net == NET_BF16) word = pack_word_lp<__bf16>(sh, raw, q);
     else if (sh.net == NET_F16X2) word = pack_word_lp<_Float16>(sh, raw, q);
+    else if (sh.net == NET_F32_VALU) word = __float_as_uint(pack_word_valu(sh, raw, q));
     else word = __float_as_uint(pack_word_f32(sh, raw, q));
     pp.packed[x] = word;
   }
@@ -185,8 +187,16 @@ static int make_shape(const tuner_space* sp, const tuner_model* m, Shape* sh) {
     sh->o_b2 = sh->o_b1 + sh->NT1 * 32;
     sh->o_wo = sh->o_b2 + sh->NT2 * 32;
     sh->member_words = sh->o_wo + ntl * 32;
-  } else {
-    return set_error(TUNER_EINVAL, "the plain vector-ALU variant is not built yet");
+  } else {                                     // NET_F32_VALU
+    sh->NPL = 1;
+    sh->KS = sh->P <= 8 ? 8 : (sh->P <= 16 ? 16 : 32);   // inputs padded
+    const int h1p = sh->NT1 * 32, h2p = sh->NT2 * 32;
+    sh->o_w1 = 0;
+    sh->o_w2 = h1p * sh->KS;
+    sh->o_b1 = sh->o_w2 + h2p * h1p;
+    sh->o_b2 = sh->o_b1 + h1p;
+    sh->o_wo = sh->o_b2 + h2p;
+    sh->member_words = sh->o_wo + ntl * 32;
   }
   return TUNER_OK;
 }
@@ -194,6 +204,7 @@ static int make_shape(const tuner_space* sp, const tuner_model* m, Shape* sh) {
 static const Variant* find_variant(const Shape& sh) {
   if (sh.net == NET_F32_MFMA) return find_variant_f32(sh.KS, sh.NT1, sh.NT2);
   if (sh.net == NET_BF16 || sh.net == NET_F16X2) return find_variant_lp(sh.net, sh.KS, sh.NT1, sh.NT2);
+  if (sh.net == NET_F32_VALU) return find_variant_valu(sh.KS, sh.NT1, sh.NT2);
   return nullptr;
 }
 
@@ -284,7 +295,7 @@ static int run_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin
   hipLaunchKernelGGL(prep_kernel, dim3(prep_blocks), dim3(256), 0, stream, sp->dev, pp);
   TUNER_HIP_TRY(hipGetLastError());
 
-  const int iter = var->waves * var->R * 32;
+  const int iter = var->waves * var->R * var->tile;
   const uint64_t n_chunks64 = (count + iter - 1) / iter;
   const uint32_t n_chunks = (uint32_t)n_chunks64;   // count <= 2^32, iter >= 512
   const int n_cu = di.n_cu > 0 ? di.n_cu : 1;
@@ -304,7 +315,7 @@ static int run_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin
     sw.members_per_stage = mps;
     sw.n_stages = (sh.E + mps - 1) / mps;
     sw.member_words = sh.member_words;
-    sw.off = NetOffsets{sh.o_w1, sh.o_w2, sh.o_b1, sh.o_b2, sh.o_wo};
+    sw.off = NetOffsets{sh.o_w1, sh.o_w2, sh.o_b1, sh.o_b2, sh.o_wo, sh.H1, sh.H2};
     sw.mode = mode;
     sw.inv_members = (float)(1.0 / (double)sh.E);
     sw.k = k;

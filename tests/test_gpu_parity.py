@@ -158,10 +158,11 @@ TOL_BF16 = 1e-2
 def _nets():
     import paper_1506_00842_amd as T
     return {"split16": (dict(precision=T.TUNER_FP32, algo=T.TUNER_ALGO_SPLIT16), parity.TOL_FP32),
+            "valu": (dict(precision=T.TUNER_FP32, algo=T.TUNER_ALGO_VALU), parity.TOL_FP32),
             "bf16": (dict(precision=T.TUNER_BF16_MFMA, algo=T.TUNER_ALGO_AUTO), TOL_BF16)}
 
 
-@pytest.mark.parametrize("net", ["split16", "bf16"])
+@pytest.mark.parametrize("net", ["split16", "bf16", "valu"])
 @pytest.mark.parametrize("P,hidden,E", SHAPES)
 def test_other_nets_model_shapes(net, P, hidden, E):
     """Two-plane f16 split (fp32 tolerance) and bf16 operands (1e-2) on every
@@ -181,7 +182,7 @@ def test_other_nets_model_shapes(net, P, hidden, E):
         say(f"  {net} {w.name} {hidden}: worst {worst:.3f} x tol({tol:g})")
 
 
-@pytest.mark.parametrize("net", ["split16", "bf16"])
+@pytest.mark.parametrize("net", ["split16", "bf16", "valu"])
 def test_other_nets_benchmark_workloads(net):
     kw, tol = _nets()[net]
     for maker, begin, count in ((wl.tiny, 0, 256), (wl.conv_shaped, 0, 393216),
@@ -213,7 +214,7 @@ def test_split16_saturation_and_zero_weights():
     b1[:15] = 1e4
     b1[15:] = -1e4
     wo[:] = 1.0
-    for kw in (dict(algo=T.TUNER_ALGO_SPLIT16), dict(precision=T.TUNER_BF16_MFMA)):
+    for kw in (dict(algo=T.TUNER_ALGO_SPLIT16), dict(precision=T.TUNER_BF16_MFMA), dict(algo=T.TUNER_ALGO_VALU)):
         sw = sweep_for(wl.Workload("sat", w.space, big, 5), **kw)
         pred, mask = sw.predict_all(0, 4096)
         torch.cuda.synchronize()
