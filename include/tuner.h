@@ -62,7 +62,7 @@ enum { TUNER_ALGO_AUTO = 0, TUNER_ALGO_MFMA = 1, TUNER_ALGO_VALU = 2, TUNER_ALGO
 
 /* Limits of this build. */
 #define TUNER_MAX_PARAMS 31       /* P */
-#define TUNER_MAX_VALUES 256      /* sum of the list lengths */
+#define TUNER_MAX_VALUES 254      /* sum of the list lengths */
 #define TUNER_MAX_CONSTRAINTS 8
 #define TUNER_MAX_CONSTRAINT_ENTRIES 64 /* (rule, parameter) pairs with a non-zero term */
 #define TUNER_MAX_TERM_WORDS 256  /* total length of the non-zero term tables */

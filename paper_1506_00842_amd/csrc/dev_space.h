@@ -16,11 +16,24 @@
 
 namespace tuner {
 
-constexpr int kMaxParams = 32;   // array length (31 usable + bias slot)
+constexpr int kMaxParams = 32;   // array length (31 usable + one padding slot)
 constexpr int kMaxValues = 256;
 constexpr int kMaxCons = 8;
 constexpr int kMaxEntries = 64;
 constexpr int kMaxTermWords = 256;
+
+// Per-parameter decode constants, one 16-byte and one 8-byte LDS read per digit.
+// digit_p(i) = (i / stride_p) mod radix_p.  Division by an invariant integer through
+// multiply-high and shifts (Granlund & Montgomery 1994):
+//   t = mulhi(mul, n);  q = (t + ((n - t) >> sh1)) >> sh2
+// *_sh packs sh1 | sh2 << 8 | log2(divisor) << 16 (the last only if the divisor is a
+// power of two).  Entries past n_params describe a one-value parameter whose feature is
+// 0 (digit always 0, lut_off = kLutZero).
+struct ParamA { uint32_t stride_sh, radix, lut_off, stride_mul; };
+struct ParamB { uint32_t radix_mul, radix_sh; };
+
+constexpr int kLutZero = kMaxValues - 2;   // lut[kLutZero] = 0.0f
+constexpr int kLutOne = kMaxValues - 1;    // lut[kLutOne] = 1.0f
 
 // Passed to kernels by value (about 3.1 KB) and copied to LDS by the sweep.
 struct DevSpace {
@@ -28,23 +41,15 @@ struct DevSpace {
   int32_t n_constraints;
   int32_t all_pow2;      // every stride and radix is a power of two
   int32_t pad0;
-  // digit_p(i) = (i / stride_p) mod radix_p.  Division by an invariant
-  // integer through multiply-high and shifts (Granlund & Montgomery 1994):
-  //   t = mulhi(mul, n);  q = (t + ((n - t) >> sh1)) >> sh2
-  // *_sh packs sh1 | sh2 << 8 | log2(divisor) << 16 (the last only if pow2).
-  uint32_t stride_mul[kMaxParams];
-  uint32_t stride_sh[kMaxParams];
-  uint32_t radix_mul[kMaxParams];
-  uint32_t radix_sh[kMaxParams];
-  uint32_t radix[kMaxParams];
-  uint32_t lut_off[kMaxParams];       // start of the parameter's features in lut[]
+  ParamA pa[kMaxParams];
+  ParamB pb[kMaxParams];
   // validity rule c uses entries [entry_begin[c], entry_begin[c+1]); an entry
   // names a parameter and the start of its term table in terms[].
   uint32_t entry[kMaxEntries];        // param | term_off << 8
   int32_t entry_begin[kMaxCons + 1];
   int32_t bound[kMaxCons];
   int32_t pad1[3];
-  float lut[kMaxValues];              // normalised fp32 features
+  float lut[kMaxValues];              // normalised fp32 features (+ the two constants)
   int32_t terms[kMaxTermWords];       // non-zero term tables, back to back
 };
 
@@ -61,37 +66,42 @@ TUNER_HD uint32_t fast_div(uint32_t n, uint32_t mul, uint32_t sh) {
   return (t + ((n - t) >> (sh & 0xffu))) >> ((sh >> 8) & 0xffu);
 }
 
-// S may live in LDS, in kernel-argument memory or on the host.
+// S may live in LDS, in kernel-argument memory or on the host.  pow2 = s.all_pow2,
+// hoisted by the caller.
 template <class S>
-TUNER_HD uint32_t digit_of(const S& s, int p, uint32_t index) {
-  if (s.all_pow2) {
-    return (index >> (s.stride_sh[p] >> 16)) & (s.radix[p] - 1u);
-  }
-  const uint32_t q = fast_div(index, s.stride_mul[p], s.stride_sh[p]);
-  return q - fast_div(q, s.radix_mul[p], s.radix_sh[p]) * s.radix[p];
+TUNER_HD uint32_t digit_of(const S& s, int p, uint32_t index, bool pow2, uint32_t* lut_off = nullptr) {
+  const ParamA a = s.pa[p];
+  if (lut_off) *lut_off = a.lut_off;
+  if (pow2) return (index >> (a.stride_sh >> 16)) & (a.radix - 1u);
+  const ParamB b = s.pb[p];
+  const uint32_t q = fast_div(index, a.stride_mul, a.stride_sh);
+  return q - fast_div(q, b.radix_mul, b.radix_sh) * a.radix;
 }
 
+// fp32 network input of parameter p for configuration `index`
 template <class S>
-TUNER_HD float feature_of(const S& s, int p, uint32_t digit) {
-  return s.lut[s.lut_off[p] + digit];
+TUNER_HD float feature_at(const S& s, int p, uint32_t index, bool pow2) {
+  uint32_t off;
+  const uint32_t d = digit_of(s, p, index, pow2, &off);
+  return s.lut[off + d];
 }
 
 // Sum of rule c's terms over the entries e = first, first+step, ... of the rule.
 template <class S>
-TUNER_HD int32_t rule_partial_sum(const S& s, int c, uint32_t index, int first, int step) {
+TUNER_HD int32_t rule_partial_sum(const S& s, int c, uint32_t index, int first, int step, bool pow2) {
   int32_t sum = 0;
   for (int e = s.entry_begin[c] + first; e < s.entry_begin[c + 1]; e += step) {
     const uint32_t ent = s.entry[e];
     const int p = (int)(ent & 0xffu);
-    sum += s.terms[(ent >> 8) + digit_of(s, p, index)];
+    sum += s.terms[(ent >> 8) + digit_of(s, p, index, pow2)];
   }
   return sum;
 }
 
 template <class S>
-TUNER_HD bool is_valid(const S& s, uint32_t index) {
+TUNER_HD bool is_valid(const S& s, uint32_t index, bool pow2) {
   bool ok = true;
-  for (int c = 0; c < s.n_constraints; ++c) ok = ok && (rule_partial_sum(s, c, index, 0, 1) <= s.bound[c]);
+  for (int c = 0; c < s.n_constraints; ++c) ok = ok && (rule_partial_sum(s, c, index, 0, 1, pow2) <= s.bound[c]);
   return ok;
 }
 

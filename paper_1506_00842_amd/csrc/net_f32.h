@@ -29,15 +29,17 @@ struct F32Net {
   static constexpr int kTile = 32;
   struct Feat { float x[KS1]; };   // B operand of layer 1: feature 2 s + h, 1.0 in the bias slot
 
-  static __device__ __forceinline__ void load_features(const DevSpace& sp, uint32_t i, int lane, Feat& f) {
+  // branch-free: slots past the last parameter decode to feature 0, the slot right
+  // after it carries the constant 1 that multiplies the bias column
+  static __device__ __forceinline__ void load_features(const DevSpace& sp, uint32_t i, int lane, bool pow2,
+                                                       Feat& f) {
     const int h = lane >> 5;
+    const int n_params = sp.n_params;
 #pragma unroll
     for (int s = 0; s < KS1; ++s) {
       const int p = 2 * s + h;
-      float v = 0.0f;
-      if (p < sp.n_params) v = feature_of(sp, p, digit_of(sp, p, i));
-      else if (p == sp.n_params) v = 1.0f;
-      f.x[s] = v;
+      const float v = feature_at(sp, p, i, pow2);
+      f.x[s] = (p == n_params) ? 1.0f : v;
     }
   }
   static __device__ __forceinline__ void zero_features(Feat& f) {

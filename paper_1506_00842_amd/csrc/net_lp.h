@@ -74,15 +74,15 @@ struct LpNet {
   static constexpr int kTile = 32;
   struct Feat { B4 x[NPL][KB1]; };
 
-  static __device__ __forceinline__ void load_features(const DevSpace& sp, uint32_t i, int lane, Feat& f) {
+  static __device__ __forceinline__ void load_features(const DevSpace& sp, uint32_t i, int lane, bool pow2,
+                                                       Feat& f) {
     const int h = lane >> 5;
 #pragma unroll
     for (int kb = 0; kb < KB1; ++kb) {
       float v[8];
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
-        const int p = 16 * kb + 8 * h + j;
-        v[j] = (p < sp.n_params) ? feature_of(sp, p, digit_of(sp, p, i)) : 0.0f;
+        v[j] = feature_at(sp, 16 * kb + 8 * h + j, i, pow2);   // 0 past the last parameter
       }
 #pragma unroll
       for (int jj = 0; jj < 4; ++jj) {

@@ -19,10 +19,10 @@ struct ValuNet {
   static constexpr int kTile = 64;
   struct Feat { float x[PMAX]; };
 
-  static __device__ __forceinline__ void load_features(const DevSpace& sp, uint32_t i, int lane, Feat& f) {
+  static __device__ __forceinline__ void load_features(const DevSpace& sp, uint32_t i, int lane, bool pow2,
+                                                       Feat& f) {
 #pragma unroll
-    for (int p = 0; p < PMAX; ++p)
-      f.x[p] = (p < sp.n_params) ? feature_of(sp, p, digit_of(sp, p, i)) : 0.0f;
+    for (int p = 0; p < PMAX; ++p) f.x[p] = feature_at(sp, p, i, pow2);   // 0 past the last parameter
   }
   static __device__ __forceinline__ void zero_features(Feat& f) {
 #pragma unroll

@@ -10,7 +10,7 @@
 //                                                 configuration is shared by the lane pair
 //                                                 (lane, lane ^ 32)) or 64 (one per lane)
 //   struct Feat                                   per-tile network input registers
-//   static void load_features(sp, index, lane, Feat&)
+//   static void load_features(sp, index, lane, pow2, Feat&)
 //   static void zero_features(Feat&)
 //   static float forward(const uint32_t* member_lds, const Feat&, int lane, const NetOffsets&)
 //        -> the lane's share of the member's output (both halves of a lane pair
@@ -53,6 +53,8 @@ __global__ void __launch_bounds__(NW * 64) sweep_kernel(const SweepParams prm) {
   };
   if (prm.n_stages == 1) load_stage(0);
   const float bo_sum = prm.hdr->bo_sum;
+  const bool pow2 = prm.space->all_pow2 != 0;
+  const int n_constraints = prm.space->n_constraints;
   // the weight stage doubles as sort scratch during pool compaction
   unsigned long long* lds_keys = reinterpret_cast<unsigned long long*>(wts);
   const uint32_t lds_entries = (uint32_t)prm.members_per_stage * (uint32_t)prm.member_words / 2u;
@@ -111,20 +113,20 @@ __global__ void __launch_bounds__(NW * 64) sweep_kernel(const SweepParams prm) {
       const uint32_t i = (uint32_t)(prm.begin + (in_range ? p0 : prm.count - 1));
       idx[r] = i;
       bool v = in_range;
-      for (int cc = 0; cc < sp.n_constraints; ++cc) {
+      for (int cc = 0; cc < n_constraints; ++cc) {
         int ps;
         if constexpr (kTile == 32) {
-          ps = rule_partial_sum(sp, cc, i, h, 2);     // the lane pair splits the rule's entries
+          ps = rule_partial_sum(sp, cc, i, h, 2, pow2);     // the lane pair splits the rule's entries
           ps += __shfl_xor(ps, 32);
         } else {
-          ps = rule_partial_sum(sp, cc, i, 0, 1);
+          ps = rule_partial_sum(sp, cc, i, 0, 1, pow2);
         }
         v = v && (ps <= sp.bound[cc]);
       }
       ok[r] = v;
       any[r] = __ballot(v) != 0ull;
       ysum[r] = 0.0f;
-      if (any[r]) Net::load_features(sp, i, lane, feat[r]);
+      if (any[r]) Net::load_features(sp, i, lane, pow2, feat[r]);
       else Net::zero_features(feat[r]);
     }
 

@@ -83,6 +83,7 @@ int tuner_space_create(int32_t n_params, const int32_t* radices, const double* v
         return set_error(TUNER_ETOOLARGE, "more than 2^32 configurations");
     }
     if (total > TUNER_MAX_VALUES) return set_error(TUNER_ETOOLARGE, "too many values");
+    static_assert(TUNER_MAX_VALUES == tuner::kMaxValues - 2, "two table slots hold the constants 0 and 1");
     sp->total_values = total;
     sp->n_configs = (uint64_t)n;
     sp->radices.assign(radices, radices + n_params);
@@ -102,14 +103,22 @@ int tuner_space_create(int32_t n_params, const int32_t* radices, const double* v
         return set_error(TUNER_EINVAL, "bad scale flag");
       if (!tuner::is_pow2((uint64_t)radices[p])) d.all_pow2 = 0;
     }
+    d.lut[tuner::kLutZero] = 0.0f;
+    d.lut[tuner::kLutOne] = 1.0f;
+    for (int p = n_params; p < tuner::kMaxParams; ++p) {     // padding: digit 0, feature 0
+      tuner::div_constants(1u, &d.pa[p].stride_mul, &d.pa[p].stride_sh);
+      tuner::div_constants(1u, &d.pb[p].radix_mul, &d.pb[p].radix_sh);
+      d.pa[p].radix = 1u;
+      d.pa[p].lut_off = (uint32_t)tuner::kLutZero;
+    }
     for (int p = 0; p < n_params; ++p) {
       // a one-value parameter always decodes to digit 0: give it stride 1 so
       // that every stride fits in 32 bits
       const uint64_t stride = radices[p] == 1 ? 1 : sp->strides[p];
-      tuner::div_constants((uint32_t)stride, &d.stride_mul[p], &d.stride_sh[p]);
-      tuner::div_constants((uint32_t)radices[p], &d.radix_mul[p], &d.radix_sh[p]);
-      d.radix[p] = (uint32_t)radices[p];
-      d.lut_off[p] = (uint32_t)sp->offsets[p];
+      tuner::div_constants((uint32_t)stride, &d.pa[p].stride_mul, &d.pa[p].stride_sh);
+      tuner::div_constants((uint32_t)radices[p], &d.pb[p].radix_mul, &d.pb[p].radix_sh);
+      d.pa[p].radix = (uint32_t)radices[p];
+      d.pa[p].lut_off = (uint32_t)sp->offsets[p];
       // feature table
       const int r = radices[p];
       std::vector<double> t(r);
@@ -218,12 +227,12 @@ int tuner_space_decode_device_arith(const tuner_space* sp, uint64_t index, int32
   if (!sp || !digits) return set_error(TUNER_EINVAL, "null argument");
   if (index >= sp->n_configs) return set_error(TUNER_EINVAL, "index outside the space");
   const uint32_t i = (uint32_t)index;
+  const bool pow2 = sp->dev.all_pow2 != 0;
   for (int p = 0; p < sp->n_params; ++p) {
-    const uint32_t dgt = tuner::digit_of(sp->dev, p, i);
-    digits[p] = (int32_t)dgt;
-    if (features) features[p] = tuner::feature_of(sp->dev, p, dgt);
+    digits[p] = (int32_t)tuner::digit_of(sp->dev, p, i, pow2);
+    if (features) features[p] = tuner::feature_at(sp->dev, p, i, pow2);
   }
-  if (valid) *valid = tuner::is_valid(sp->dev, i) ? 1 : 0;
+  if (valid) *valid = tuner::is_valid(sp->dev, i, pow2) ? 1 : 0;
   return TUNER_OK;
 }
 
@@ -241,12 +250,12 @@ decode_range_kernel(const DevSpace sp, uint64_t begin, uint64_t count, int32_t* 
   if (t >= count) return;
   const uint32_t i = (uint32_t)(begin + t);
   const int P = sp.n_params;
+  const bool pow2 = sp.all_pow2 != 0;
   for (int p = 0; p < P; ++p) {
-    const uint32_t d = digit_of(sp, p, i);
-    if (digits) digits[t * P + p] = (int32_t)d;
-    if (features) features[t * P + p] = feature_of(sp, p, d);
+    if (digits) digits[t * P + p] = (int32_t)digit_of(sp, p, i, pow2);
+    if (features) features[t * P + p] = feature_at(sp, p, i, pow2);
   }
-  if (valid) valid[t] = is_valid(sp, i) ? 1 : 0;
+  if (valid) valid[t] = is_valid(sp, i, pow2) ? 1 : 0;
 }
 
 }  // namespace tuner
