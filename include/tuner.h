@@ -65,7 +65,7 @@ enum { TUNER_ALGO_AUTO = 0, TUNER_ALGO_MFMA = 1, TUNER_ALGO_VALU = 2, TUNER_ALGO
 #define TUNER_MAX_VALUES 254      /* sum of the list lengths */
 #define TUNER_MAX_CONSTRAINTS 8
 #define TUNER_MAX_CONSTRAINT_ENTRIES 64 /* (rule, parameter) pairs with a non-zero term */
-#define TUNER_MAX_TERM_WORDS 256  /* total length of the non-zero term tables */
+#define TUNER_MAX_TERM_WORDS 192  /* total length of the non-zero term tables */
 #define TUNER_MAX_WIDTH 128       /* hidden-layer width */
 #define TUNER_MAX_K 16384
 

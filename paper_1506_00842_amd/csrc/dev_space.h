@@ -20,22 +20,25 @@ constexpr int kMaxParams = 32;   // array length (31 usable + one padding slot)
 constexpr int kMaxValues = 256;
 constexpr int kMaxCons = 8;
 constexpr int kMaxEntries = 64;
-constexpr int kMaxTermWords = 256;
+constexpr int kMaxTermWords = 192;
 
-// Per-parameter decode constants, one 16-byte and one 8-byte LDS read per digit.
-// digit_p(i) = (i / stride_p) mod radix_p.  Division by an invariant integer through
-// multiply-high and shifts (Granlund & Montgomery 1994):
-//   t = mulhi(mul, n);  q = (t + ((n - t) >> sh1)) >> sh2
-// *_sh packs sh1 | sh2 << 8 | log2(divisor) << 16 (the last only if the divisor is a
-// power of two).  Entries past n_params describe a one-value parameter whose feature is
-// 0 (digit always 0, lut_off = kLutZero).
-struct ParamA { uint32_t stride_sh, radix, lut_off, stride_mul; };
-struct ParamB { uint32_t radix_mul, radix_sh; };
+// Decode constants of one parameter.  digit_p(i) = (i / stride_p) mod radix_p.
+//   power-of-two spaces:  digit = (i >> shift) & mask
+//   otherwise: division by an invariant integer through multiply-high and shifts
+//   (Granlund & Montgomery 1994):  t = mulhi(mul, n);  q = (t + ((n - t) >> sh1)) >> sh2,
+//   with *_sh = sh1 | sh2 << 8.
+// The A half is all the power-of-two path reads (one 16-byte LDS read per digit).
+// Slots past n_params describe a one-value parameter whose feature is 0.
+struct ParamA { uint32_t shift, mask, lut_off4, stride_mul; };   // lut_off4: byte offset into lut[]
+struct ParamB { uint32_t stride_sh, radix_mul, radix_sh, radix; };
+// A validity-rule entry = one parameter with a non-zero term table.
+struct RuleEntry { uint32_t param, term_off4; };                // byte offset into terms[]
 
 constexpr int kLutZero = kMaxValues - 2;   // lut[kLutZero] = 0.0f
 constexpr int kLutOne = kMaxValues - 1;    // lut[kLutOne] = 1.0f
 
-// Passed to kernels by value (about 3.1 KB) and copied to LDS by the sweep.
+// Passed to kernels by value (3.4 KB; the kernel-argument limit is 4 KB) and copied to
+// LDS by the sweep.
 struct DevSpace {
   int32_t n_params;
   int32_t n_constraints;
@@ -43,15 +46,15 @@ struct DevSpace {
   int32_t pad0;
   ParamA pa[kMaxParams];
   ParamB pb[kMaxParams];
-  // validity rule c uses entries [entry_begin[c], entry_begin[c+1]); an entry
-  // names a parameter and the start of its term table in terms[].
-  uint32_t entry[kMaxEntries];        // param | term_off << 8
+  // validity rule c uses entries [entry_begin[c], entry_begin[c+1])
+  RuleEntry entry[kMaxEntries];
   int32_t entry_begin[kMaxCons + 1];
   int32_t bound[kMaxCons];
   int32_t pad1[3];
   float lut[kMaxValues];              // normalised fp32 features (+ the two constants)
   int32_t terms[kMaxTermWords];       // non-zero term tables, back to back
 };
+static_assert(sizeof(DevSpace) <= 3584, "DevSpace must leave room in the 4 KB kernel-argument block");
 
 TUNER_HD uint32_t mulhi_u32(uint32_t a, uint32_t b) {
 #if defined(__HIP_DEVICE_COMPILE__)
@@ -66,34 +69,51 @@ TUNER_HD uint32_t fast_div(uint32_t n, uint32_t mul, uint32_t sh) {
   return (t + ((n - t) >> (sh & 0xffu))) >> ((sh >> 8) & 0xffu);
 }
 
+// Any 32-bit index decodes to an in-range digit (the top parameter wraps), so lanes
+// past the end of a range may decode safely.
+TUNER_HD uint32_t digit_from(const ParamA& a, const ParamB& b, uint32_t index, bool pow2) {
+  if (pow2) return (index >> a.shift) & a.mask;
+  const uint32_t q = fast_div(index, a.stride_mul, b.stride_sh);
+  return q - fast_div(q, b.radix_mul, b.radix_sh) * b.radix;
+}
+
+TUNER_HD uint32_t word_at(const void* table, uint32_t byte_off) {
+  return *reinterpret_cast<const uint32_t*>(static_cast<const char*>(table) + byte_off);
+}
+
 // S may live in LDS, in kernel-argument memory or on the host.  pow2 = s.all_pow2,
 // hoisted by the caller.
 template <class S>
-TUNER_HD uint32_t digit_of(const S& s, int p, uint32_t index, bool pow2, uint32_t* lut_off = nullptr) {
-  const ParamA a = s.pa[p];
-  if (lut_off) *lut_off = a.lut_off;
-  if (pow2) return (index >> (a.stride_sh >> 16)) & (a.radix - 1u);
-  const ParamB b = s.pb[p];
-  const uint32_t q = fast_div(index, a.stride_mul, a.stride_sh);
-  return q - fast_div(q, b.radix_mul, b.radix_sh) * a.radix;
+TUNER_HD uint32_t digit_of(const S& s, int p, uint32_t index, bool pow2) {
+  if (pow2) return digit_from(s.pa[p], ParamB{}, index, true);
+  return digit_from(s.pa[p], s.pb[p], index, false);
 }
 
 // fp32 network input of parameter p for configuration `index`
 template <class S>
 TUNER_HD float feature_at(const S& s, int p, uint32_t index, bool pow2) {
-  uint32_t off;
-  const uint32_t d = digit_of(s, p, index, pow2, &off);
-  return s.lut[off + d];
+  const ParamA a = s.pa[p];
+  uint32_t d;
+  if (pow2) d = digit_from(a, ParamB{}, index, true);
+  else d = digit_from(a, s.pb[p], index, false);
+  const uint32_t bits = word_at(s.lut, a.lut_off4 + 4u * d);
+#if defined(__HIP_DEVICE_COMPILE__)
+  return __uint_as_float(bits);
+#else
+  float f;
+  __builtin_memcpy(&f, &bits, 4);
+  return f;
+#endif
 }
 
 // Sum of rule c's terms over the entries e = first, first+step, ... of the rule.
 template <class S>
 TUNER_HD int32_t rule_partial_sum(const S& s, int c, uint32_t index, int first, int step, bool pow2) {
   int32_t sum = 0;
-  for (int e = s.entry_begin[c] + first; e < s.entry_begin[c + 1]; e += step) {
-    const uint32_t ent = s.entry[e];
-    const int p = (int)(ent & 0xffu);
-    sum += s.terms[(ent >> 8) + digit_of(s, p, index, pow2)];
+  const int end = s.entry_begin[c + 1];
+  for (int e = s.entry_begin[c] + first; e < end; e += step) {
+    const RuleEntry ent = s.entry[e];
+    sum += (int32_t)word_at(s.terms, ent.term_off4 + 4u * digit_of(s, (int)ent.param, index, pow2));
   }
   return sum;
 }

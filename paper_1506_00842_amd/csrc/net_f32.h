@@ -29,22 +29,28 @@ struct F32Net {
   static constexpr int kTile = 32;
   struct Feat { float x[KS1]; };   // B operand of layer 1: feature 2 s + h, 1.0 in the bias slot
 
-  // branch-free: slots past the last parameter decode to feature 0, the slot right
-  // after it carries the constant 1 that multiplies the bias column
+  // branch-free: slots past the last parameter decode to feature 0; the slot right
+  // after it decodes to the constant 1 that multiplies the bias column (the prep kernel
+  // points that slot of the table at the constant)
+  static constexpr bool kBiasInput = true;
   static __device__ __forceinline__ void load_features(const DevSpace& sp, uint32_t i, int lane, bool pow2,
                                                        Feat& f) {
     const int h = lane >> 5;
-    const int n_params = sp.n_params;
 #pragma unroll
-    for (int s = 0; s < KS1; ++s) {
-      const int p = 2 * s + h;
-      const float v = feature_at(sp, p, i, pow2);
-      f.x[s] = (p == n_params) ? 1.0f : v;
-    }
+    for (int s = 0; s < KS1; ++s) f.x[s] = feature_at(sp, 2 * s + h, i, pow2);
   }
   static __device__ __forceinline__ void zero_features(Feat& f) {
 #pragma unroll
     for (int s = 0; s < KS1; ++s) f.x[s] = 0.0f;
+  }
+
+  static __device__ __forceinline__ void sigmoid16(floatx16& a) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) a[v] = __builtin_amdgcn_exp2f(a[v]);
+#pragma unroll
+    for (int v = 0; v < 16; ++v) a[v] = 1.0f + a[v];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) a[v] = __builtin_amdgcn_rcpf(a[v]);
   }
 
   static __device__ __forceinline__ float forward(const uint32_t* __restrict__ wm, const Feat& f, int lane,
@@ -68,10 +74,13 @@ struct F32Net {
         a1[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, f.x[4 * sg + 3], a1[t], 0, 0, 0);
       }
     }
+    // sigmoid in three passes (exp2, +1, rcp) so that no instruction waits on the
+    // transcendental that precedes it; fp32 MFMA and VALU work do not overlap on a
+    // SIMD, so nothing is gained by interleaving them
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int t = 0; t < NT1; ++t)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) a1[t][v] = sigmoid_prescaled(a1[t][v]);
+    for (int t = 0; t < NT1; ++t) sigmoid16(a1[t]);
+    __builtin_amdgcn_sched_barrier(0);
 
     float part = 0.0f;
     if constexpr (NT2 > 0) {
@@ -98,15 +107,19 @@ struct F32Net {
             a2[u] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, a1[t][4 * g + 3], a2[u], 0, 0, 0);
           }
       const float4* wo = reinterpret_cast<const float4*>(w + o.wo);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int u = 0; u < NT2; ++u) sigmoid16(a2[u]);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int u = 0; u < NT2; ++u)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
           const float4 q = wo[(u * 4 + g) * 2 + h];
-          part = fmaf(q.x, sigmoid_prescaled(a2[u][4 * g + 0]), part);
-          part = fmaf(q.y, sigmoid_prescaled(a2[u][4 * g + 1]), part);
-          part = fmaf(q.z, sigmoid_prescaled(a2[u][4 * g + 2]), part);
-          part = fmaf(q.w, sigmoid_prescaled(a2[u][4 * g + 3]), part);
+          part = fmaf(q.x, a2[u][4 * g + 0], part);
+          part = fmaf(q.y, a2[u][4 * g + 1], part);
+          part = fmaf(q.z, a2[u][4 * g + 2], part);
+          part = fmaf(q.w, a2[u][4 * g + 3], part);
         }
     } else {
       const float4* wo = reinterpret_cast<const float4*>(w + o.wo);

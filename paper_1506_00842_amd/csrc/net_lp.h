@@ -74,6 +74,7 @@ struct LpNet {
   static constexpr int kTile = 32;
   struct Feat { B4 x[NPL][KB1]; };
 
+  static constexpr bool kBiasInput = false;
   static __device__ __forceinline__ void load_features(const DevSpace& sp, uint32_t i, int lane, bool pow2,
                                                        Feat& f) {
     const int h = lane >> 5;

@@ -19,6 +19,7 @@ struct ValuNet {
   static constexpr int kTile = 64;
   struct Feat { float x[PMAX]; };
 
+  static constexpr bool kBiasInput = false;
   static __device__ __forceinline__ void load_features(const DevSpace& sp, uint32_t i, int lane, bool pow2,
                                                        Feat& f) {
 #pragma unroll

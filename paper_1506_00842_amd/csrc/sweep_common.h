@@ -11,6 +11,7 @@ namespace tuner {
 constexpr int kMergeThreads = 1024;
 constexpr int kMaxGroups = 256;           // persistent workgroups (MI355X: 256 CUs)
 constexpr int kMaxIter = 1024;            // most configurations per chunk (waves * R * tile) over all variants
+constexpr int kMaxSuper = 4;              // most chunks per queue unit
 constexpr unsigned long long kKeyMax = ~0ull;
 constexpr int kSpaceBytes = (sizeof(DevSpace) + 255) / 256 * 256;
 constexpr float kNegLog2e = -1.44269504088896340736f;
@@ -44,7 +45,8 @@ struct NetOffsets { int w1, w2, b1, b2, wo, h1, h2; };   // word offsets; real h
 
 struct SweepParams {
   uint64_t begin, count;
-  uint32_t n_chunks;
+  uint32_t n_chunks, n_units;  // chunks of waves*R*tile configurations; queue units of `super` chunks
+  int32_t super;
   int32_t n_members, members_per_stage, n_stages, member_words;
   int32_t mode, k;
   float inv_members;          // 1 / n_members, rounded once from double

@@ -20,6 +20,17 @@
 
 namespace tuner {
 
+// x[lane] + x[lane ^ 32] in every lane (v_permlane32_swap exchanges the upper 32 lanes
+// of its first operand with the lower 32 lanes of its second)
+__device__ __forceinline__ float pair_sum(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+__device__ __forceinline__ int pair_sum(int x) {
+  const auto r = __builtin_amdgcn_permlane32_swap((unsigned)x, (unsigned)x, false, false);
+  return (int)(r[0] + r[1]);
+}
+
 template <class Net, int R, int NW>
 __global__ void __launch_bounds__(NW * 64) sweep_kernel(const SweepParams prm) {
   constexpr int kThreads = NW * 64;
@@ -32,7 +43,8 @@ __global__ void __launch_bounds__(NW * 64) sweep_kernel(const SweepParams prm) {
 
   constexpr int kTile = Net::kTile;
   constexpr int kIter = kWaves * R * kTile;   // configurations per chunk
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave_u = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave index, known uniform
   const int c = kTile == 32 ? (lane & 31) : lane, h = kTile == 32 ? (lane >> 5) : 0;
   unsigned long long* pool = prm.pools + (size_t)blockIdx.x * prm.cap;
 
@@ -58,25 +70,40 @@ __global__ void __launch_bounds__(NW * 64) sweep_kernel(const SweepParams prm) {
   // the weight stage doubles as sort scratch during pool compaction
   unsigned long long* lds_keys = reinterpret_cast<unsigned long long*>(wts);
   const uint32_t lds_entries = (uint32_t)prm.members_per_stage * (uint32_t)prm.member_words / 2u;
-  // thread 0 keeps one chunk index in flight so the queue's latency is hidden
-  uint32_t next_chunk = 0;
-  if (tid == 0) next_chunk = atomicAdd(&prm.hdr->work_counter, 1u);
+  // Queue unit = prm.super consecutive chunks.  Thread 0 keeps two unit indices in
+  // flight so that the queue's latency is hidden even across runs of invalid units.
+  const uint32_t super_iter = (uint32_t)prm.super * kIter;
+  // pools are compacted while they still fit the LDS sort scratch, if that leaves room
+  uint32_t eff_cap = prm.cap;
+  {
+    uint32_t lds_pow2 = 1;
+    while (lds_pow2 * 2 <= lds_entries) lds_pow2 *= 2;
+    if (lds_pow2 < eff_cap && lds_pow2 >= 2u * prm.kp + super_iter) eff_cap = lds_pow2;
+  }
+  uint32_t next0 = 0, next1 = 0;
+  if (tid == 0) {
+    next0 = atomicAdd(&prm.hdr->work_counter, 1u);
+    next1 = atomicAdd(&prm.hdr->work_counter, 1u);
+  }
 
   for (;;) {
     __syncthreads();
     if (tid == 0) {
-      s_chunk = next_chunk;
+      s_chunk = next0;
       if (prm.mode == MODE_TOPK) {
         const unsigned long long g =
             __hip_atomic_load(&prm.hdr->tau, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         s_tau = g < s_tau_local ? g : s_tau_local;
-        s_compact = (s_cnt + kIter > prm.cap) ? 1u : 0u;
+        s_compact = (s_cnt + super_iter > eff_cap) ? 1u : 0u;
       }
     }
     __syncthreads();
-    const uint32_t chunk = s_chunk;
-    if (chunk >= prm.n_chunks) break;
-    if (tid == 0) next_chunk = atomicAdd(&prm.hdr->work_counter, 1u);
+    const uint32_t unit = __builtin_amdgcn_readfirstlane(s_chunk);
+    if (unit >= prm.n_units) break;
+    if (tid == 0) {
+      next0 = next1;
+      next1 = atomicAdd(&prm.hdr->work_counter, 1u);
+    }
 
     if (prm.mode == MODE_TOPK && s_compact) {
       // pool nearly full: keep its k smallest keys, lower the thresholds
@@ -99,25 +126,27 @@ __global__ void __launch_bounds__(NW * 64) sweep_kernel(const SweepParams prm) {
     }
     const unsigned long long tau = s_tau;
 
+    for (uint32_t sub = 0; sub < (uint32_t)prm.super; ++sub) {
+    const uint32_t chunk = unit * (uint32_t)prm.super + sub;
+    if (chunk >= prm.n_chunks) break;
+
     // ---- validity, then digits -> features, for this wave's R tiles
     typename Net::Feat feat[R];
     float ysum[R];
     bool ok[R], any[R];
     uint32_t idx[R];
-    uint64_t pos[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-      const uint64_t p0 = (uint64_t)chunk * kIter + (uint32_t)((wave * R + r) * kTile + c);
-      const bool in_range = p0 < prm.count;
-      pos[r] = p0;
-      const uint32_t i = (uint32_t)(prm.begin + (in_range ? p0 : prm.count - 1));
+      // uniform: tile start inside the range, and how many of its configurations exist
+      const uint64_t t0 = (uint64_t)chunk * kIter + (uint32_t)((wave_u * R + r) * kTile);
+      const uint32_t left = t0 < prm.count ? (uint32_t)min((uint64_t)kTile, prm.count - t0) : 0u;
+      const uint32_t i = (uint32_t)(prm.begin + t0) + (uint32_t)c;   // any 32-bit index decodes safely
       idx[r] = i;
-      bool v = in_range;
+      bool v = (uint32_t)c < left;
       for (int cc = 0; cc < n_constraints; ++cc) {
         int ps;
         if constexpr (kTile == 32) {
-          ps = rule_partial_sum(sp, cc, i, h, 2, pow2);     // the lane pair splits the rule's entries
-          ps += __shfl_xor(ps, 32);
+          ps = pair_sum(rule_partial_sum(sp, cc, i, h, 2, pow2));   // the lane pair splits the entries
         } else {
           ps = rule_partial_sum(sp, cc, i, 0, 1, pow2);
         }
@@ -153,12 +182,14 @@ __global__ void __launch_bounds__(NW * 64) sweep_kernel(const SweepParams prm) {
 #pragma unroll
     for (int r = 0; r < R; ++r) {
       float y = ysum[r];
-      if constexpr (kTile == 32) y += __shfl_xor(y, 32);
+      if constexpr (kTile == 32) y = pair_sum(y);
       y = (y + bo_sum) * prm.inv_members + 0.0f;
       if (prm.mode == MODE_ALL) {
-        if (h == 0 && pos[r] < prm.count) {
-          prm.pred[pos[r]] = ok[r] ? y : __builtin_inff();
-          if (prm.mask) prm.mask[pos[r]] = ok[r] ? 1 : 0;
+        const uint64_t t0 = (uint64_t)chunk * kIter + (uint32_t)((wave_u * R + r) * kTile);
+        const uint32_t left = t0 < prm.count ? (uint32_t)min((uint64_t)kTile, prm.count - t0) : 0u;
+        if (h == 0 && (uint32_t)c < left) {
+          prm.pred[t0 + (uint32_t)c] = ok[r] ? y : __builtin_inff();
+          if (prm.mask) prm.mask[t0 + (uint32_t)c] = ok[r] ? 1 : 0;
         }
       } else {
         const unsigned long long key = make_key(y, idx[r]);
@@ -172,6 +203,7 @@ __global__ void __launch_bounds__(NW * 64) sweep_kernel(const SweepParams prm) {
         }
       }
     }
+    }  // sub
   }
 
   if (prm.mode == MODE_TOPK) {

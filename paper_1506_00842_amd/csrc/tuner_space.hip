@@ -40,9 +40,21 @@ static void div_constants(uint32_t d, uint32_t* mul, uint32_t* sh) {
   const unsigned __int128 num = (unsigned __int128)(two_l - d) << 32;
   *mul = (uint32_t)(num / d) + 1u;
   const uint32_t sh1 = l < 1 ? l : 1, sh2 = l > 1 ? l - 1 : 0;
-  uint32_t packed = sh1 | (sh2 << 8);
-  if (is_pow2(d)) packed |= (uint32_t)l << 16;
-  *sh = packed;
+  *sh = sh1 | (sh2 << 8);
+}
+
+// Decode constants of a parameter with the given stride and radix; table_off4 is the
+// byte offset of its table (features or rule terms).
+static void param_constants(uint64_t stride, uint32_t radix, uint32_t table_off4, ParamA* a, ParamB* b) {
+  // a one-value parameter always decodes to digit 0: give it stride 1 so that every
+  // stride fits in 32 bits
+  if (radix == 1) stride = 1;
+  div_constants((uint32_t)stride, &a->stride_mul, &b->stride_sh);
+  div_constants(radix, &b->radix_mul, &b->radix_sh);
+  b->radix = radix;
+  a->shift = is_pow2(stride) ? (uint32_t)ceil_log2(stride) : 0u;
+  a->mask = radix - 1u;            // used on the power-of-two path only
+  a->lut_off4 = table_off4;
 }
 
 }  // namespace tuner
@@ -105,20 +117,11 @@ int tuner_space_create(int32_t n_params, const int32_t* radices, const double* v
     }
     d.lut[tuner::kLutZero] = 0.0f;
     d.lut[tuner::kLutOne] = 1.0f;
-    for (int p = n_params; p < tuner::kMaxParams; ++p) {     // padding: digit 0, feature 0
-      tuner::div_constants(1u, &d.pa[p].stride_mul, &d.pa[p].stride_sh);
-      tuner::div_constants(1u, &d.pb[p].radix_mul, &d.pb[p].radix_sh);
-      d.pa[p].radix = 1u;
-      d.pa[p].lut_off = (uint32_t)tuner::kLutZero;
-    }
+    for (int p = n_params; p < tuner::kMaxParams; ++p)       // padding: digit 0, feature 0
+      tuner::param_constants(1, 1u, 4u * (uint32_t)tuner::kLutZero, &d.pa[p], &d.pb[p]);
     for (int p = 0; p < n_params; ++p) {
-      // a one-value parameter always decodes to digit 0: give it stride 1 so
-      // that every stride fits in 32 bits
-      const uint64_t stride = radices[p] == 1 ? 1 : sp->strides[p];
-      tuner::div_constants((uint32_t)stride, &d.pa[p].stride_mul, &d.pa[p].stride_sh);
-      tuner::div_constants((uint32_t)radices[p], &d.pb[p].radix_mul, &d.pb[p].radix_sh);
-      d.pa[p].radix = (uint32_t)radices[p];
-      d.pa[p].lut_off = (uint32_t)sp->offsets[p];
+      tuner::param_constants(sp->strides[p], (uint32_t)radices[p], 4u * (uint32_t)sp->offsets[p],
+                             &d.pa[p], &d.pb[p]);
       // feature table
       const int r = radices[p];
       std::vector<double> t(r);
@@ -160,7 +163,9 @@ int tuner_space_create(int32_t n_params, const int32_t* radices, const double* v
         if (!any) continue;
         if (n_entries >= TUNER_MAX_CONSTRAINT_ENTRIES || n_words + radices[p] > TUNER_MAX_TERM_WORDS)
           return set_error(TUNER_ETOOLARGE, "validity rules need too many table entries");
-        d.entry[n_entries++] = (uint32_t)p | ((uint32_t)n_words << 8);
+        d.entry[n_entries].param = (uint32_t)p;
+        d.entry[n_entries].term_off4 = 4u * (uint32_t)n_words;
+        ++n_entries;
         for (int j = 0; j < radices[p]; ++j) d.terms[n_words++] = row[sp->offsets[p] + j];
       }
       if (abs_sum > std::numeric_limits<int32_t>::max())

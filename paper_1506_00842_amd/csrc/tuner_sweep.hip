@@ -71,6 +71,12 @@ __global__ void __launch_bounds__(256) prep_kernel(const DevSpace sp, const Prep
     const uint32_t* src = reinterpret_cast<const uint32_t*>(&sp);
     uint32_t* dst = reinterpret_cast<uint32_t*>(pp.space_out);
     for (uint32_t x = gtid; x < sizeof(DevSpace) / 4; x += gsize) dst[x] = src[x];
+    // the fp32 matrix network reads its bias column's constant 1 as the feature of the
+    // slot after the last parameter (same thread as the plain copy of that word)
+    if (sh.net == NET_F32_MFMA) {
+      const uint32_t word = (uint32_t)((const char*)&sp.pa[sh.P].lut_off4 - (const char*)&sp) / 4u;
+      if (gtid == word % gsize) pp.space_out->pa[sh.P].lut_off4 = 4u * (uint32_t)kLutOne;
+    }
   }
   // running result -> key list
   int found = 0;
@@ -224,7 +230,8 @@ static Layout make_layout(const Shape& sh, int k) {
   L.o_packed = L.o_space + kSpaceBytes;
   L.o_pools = L.o_packed + al((size_t)sh.E * sh.member_words * 4);
   L.kp = k > 0 ? host_next_pow2((uint32_t)k) : 0;
-  L.cap = k > 0 ? 4u * (L.kp > (uint32_t)kMaxIter ? L.kp : (uint32_t)kMaxIter) : 0;
+  const uint32_t unit_max = (uint32_t)(kMaxIter * kMaxSuper);
+  L.cap = k > 0 ? 4u * (L.kp > unit_max ? L.kp : unit_max) : 0;
   L.o_extra = L.o_pools + (size_t)kMaxGroups * L.cap * 8;
   L.total = L.o_extra + al((size_t)L.kp * 8);
   return L;
@@ -299,7 +306,12 @@ static int run_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin
   const uint64_t n_chunks64 = (count + iter - 1) / iter;
   const uint32_t n_chunks = (uint32_t)n_chunks64;   // count <= 2^32, iter >= 512
   const int n_cu = di.n_cu > 0 ? di.n_cu : 1;
-  uint32_t groups = (uint32_t)std::min<uint64_t>(n_chunks64, (uint64_t)std::min(n_cu, kMaxGroups));
+  const uint32_t max_groups = (uint32_t)std::min(n_cu, kMaxGroups);
+  // queue unit: up to kMaxSuper chunks, while every workgroup still gets >= 8 units
+  uint32_t super = 1;
+  while (super < (uint32_t)kMaxSuper && n_chunks64 / (2 * super) >= 8ull * max_groups) super *= 2;
+  const uint32_t n_units = (uint32_t)((n_chunks64 + super - 1) / super);
+  uint32_t groups = std::min<uint32_t>(n_units, max_groups);
 
   if (groups > 0) {
     const int budget = di.max_lds - kSpaceBytes - 64;   // 64 B of static LDS
@@ -311,6 +323,8 @@ static int run_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin
     sw.begin = begin;
     sw.count = count;
     sw.n_chunks = n_chunks;
+    sw.n_units = n_units;
+    sw.super = (int32_t)super;
     sw.n_members = sh.E;
     sw.members_per_stage = mps;
     sw.n_stages = (sh.E + mps - 1) / mps;

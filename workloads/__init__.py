@@ -400,7 +400,15 @@ def many_params(n_params: int, widths_hidden: Sequence[int], n_members: int, see
     return Workload(sp.name, sp, make_model([n_params, *widths_hidden, 1], n_members, seed), k)
 
 
+def large_with_members(n_members: int) -> Workload:
+    """The 2**27 space with a different ensemble size (kernel studies)."""
+    sp = _large_space(LARGE_RADICES, "large-2^27")
+    return Workload(f"cfg3-E{n_members}", sp, make_model([14, 64, 64, 1], n_members, 2), 1000,
+                    n_valid=63_700_992)
+
+
 BENCH_WORKLOADS = {
+    "cfg3-E1": lambda: large_with_members(1), "cfg3-E8": lambda: large_with_members(8),
     "cfg1": tiny, "cfg2": conv_shaped, "cfg3": large, "cfg4": wide, "cfg5": streamed,
     "cfg3-2^26": large_as_written,
     "paper-convolution": paper_convolution, "paper-raycasting": paper_raycasting,
