@@ -89,12 +89,13 @@ TUNER_HD uint32_t digit_of(const S& s, int p, uint32_t index, bool pow2) {
   return digit_from(s.pa[p], s.pb[p], index, false);
 }
 
-// fp32 network input of parameter p for configuration `index`
-template <class S>
-TUNER_HD float feature_at(const S& s, int p, uint32_t index, bool pow2) {
+// fp32 network input of parameter p for configuration `index`.  POW2 is a template
+// argument so that a caller decoding several parameters branches once, not per digit.
+template <bool POW2, class S>
+TUNER_HD float feature_at_t(const S& s, int p, uint32_t index) {
   const ParamA a = s.pa[p];
   uint32_t d;
-  if (pow2) d = digit_from(a, ParamB{}, index, true);
+  if (POW2) d = digit_from(a, ParamB{}, index, true);
   else d = digit_from(a, s.pb[p], index, false);
   const uint32_t bits = word_at(s.lut, a.lut_off4 + 4u * d);
 #if defined(__HIP_DEVICE_COMPILE__)
@@ -104,6 +105,11 @@ TUNER_HD float feature_at(const S& s, int p, uint32_t index, bool pow2) {
   __builtin_memcpy(&f, &bits, 4);
   return f;
 #endif
+}
+
+template <class S>
+TUNER_HD float feature_at(const S& s, int p, uint32_t index, bool pow2) {
+  return pow2 ? feature_at_t<true>(s, p, index) : feature_at_t<false>(s, p, index);
 }
 
 // Sum of rule c's terms over the entries e = first, first+step, ... of the rule.

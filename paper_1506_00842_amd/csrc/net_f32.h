@@ -36,8 +36,13 @@ struct F32Net {
   static __device__ __forceinline__ void load_features(const DevSpace& sp, uint32_t i, int lane, bool pow2,
                                                        Feat& f) {
     const int h = lane >> 5;
+    if (pow2) {
 #pragma unroll
-    for (int s = 0; s < KS1; ++s) f.x[s] = feature_at(sp, 2 * s + h, i, pow2);
+      for (int s = 0; s < KS1; ++s) f.x[s] = feature_at_t<true>(sp, 2 * s + h, i);
+    } else {
+#pragma unroll
+      for (int s = 0; s < KS1; ++s) f.x[s] = feature_at_t<false>(sp, 2 * s + h, i);
+    }
   }
   static __device__ __forceinline__ void zero_features(Feat& f) {
 #pragma unroll

@@ -75,16 +75,13 @@ struct LpNet {
   struct Feat { B4 x[NPL][KB1]; };
 
   static constexpr bool kBiasInput = false;
-  static __device__ __forceinline__ void load_features(const DevSpace& sp, uint32_t i, int lane, bool pow2,
-                                                       Feat& f) {
-    const int h = lane >> 5;
+  template <bool POW2>
+  static __device__ __forceinline__ void load_features_t(const DevSpace& sp, uint32_t i, int h, Feat& f) {
 #pragma unroll
     for (int kb = 0; kb < KB1; ++kb) {
       float v[8];
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        v[j] = feature_at(sp, 16 * kb + 8 * h + j, i, pow2);   // 0 past the last parameter
-      }
+      for (int j = 0; j < 8; ++j) v[j] = feature_at_t<POW2>(sp, 16 * kb + 8 * h + j, i);   // 0 past the last parameter
 #pragma unroll
       for (int jj = 0; jj < 4; ++jj) {
         uint32_t hi, lo;
@@ -93,6 +90,11 @@ struct LpNet {
         if constexpr (NPL == 2) f.x[1][kb].w[jj] = lo;
       }
     }
+  }
+  static __device__ __forceinline__ void load_features(const DevSpace& sp, uint32_t i, int lane, bool pow2,
+                                                       Feat& f) {
+    if (pow2) load_features_t<true>(sp, i, lane >> 5, f);
+    else load_features_t<false>(sp, i, lane >> 5, f);
   }
   static __device__ __forceinline__ void zero_features(Feat& f) {
 #pragma unroll

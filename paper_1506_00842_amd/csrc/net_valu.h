@@ -22,8 +22,13 @@ struct ValuNet {
   static constexpr bool kBiasInput = false;
   static __device__ __forceinline__ void load_features(const DevSpace& sp, uint32_t i, int lane, bool pow2,
                                                        Feat& f) {
+    if (pow2) {
 #pragma unroll
-    for (int p = 0; p < PMAX; ++p) f.x[p] = feature_at(sp, p, i, pow2);   // 0 past the last parameter
+      for (int p = 0; p < PMAX; ++p) f.x[p] = feature_at_t<true>(sp, p, i);   // 0 past the last parameter
+    } else {
+#pragma unroll
+      for (int p = 0; p < PMAX; ++p) f.x[p] = feature_at_t<false>(sp, p, i);
+    }
   }
   static __device__ __forceinline__ void zero_features(Feat& f) {
 #pragma unroll
