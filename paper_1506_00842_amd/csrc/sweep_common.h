@@ -51,6 +51,7 @@ struct SweepParams {
   int32_t mode, k;
   float inv_members;          // 1 / n_members, rounded once from double
   uint32_t cap, kp;           // pool capacity per workgroup, k rounded up to a power of two
+  uint32_t lds_entries;       // keys that fit the LDS region after the space tables (weights / sort scratch)
   NetOffsets off;
   const DevSpace* space;      // in the workspace
   const uint32_t* packed;

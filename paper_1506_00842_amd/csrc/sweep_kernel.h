@@ -69,7 +69,7 @@ __global__ void __launch_bounds__(NW * 64) sweep_kernel(const SweepParams prm) {
   const int n_constraints = prm.space->n_constraints;
   // the weight stage doubles as sort scratch during pool compaction
   unsigned long long* lds_keys = reinterpret_cast<unsigned long long*>(wts);
-  const uint32_t lds_entries = (uint32_t)prm.members_per_stage * (uint32_t)prm.member_words / 2u;
+  const uint32_t lds_entries = prm.lds_entries;
   // Queue unit = prm.super consecutive chunks.  Thread 0 keeps two unit indices in
   // flight so that the queue's latency is hidden even across runs of invalid units.
   const uint32_t super_iter = (uint32_t)prm.super * kIter;

@@ -341,7 +341,16 @@ static int run_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin
     sw.pools = pools;
     sw.pred = pred;
     sw.mask = mask;
-    const size_t lds = (size_t)kSpaceBytes + (size_t)mps * member_bytes;
+    // the region after the space tables holds a stage of weights and doubles as sort
+    // scratch for the candidate pool: make it large enough for a pool that is compacted
+    // when it reaches 2 k + one queue unit, if the LDS allows
+    size_t region = (size_t)mps * member_bytes;
+    if (mode == MODE_TOPK) {
+      const size_t want = 8ull * host_next_pow2(2u * L.kp + super * (uint32_t)iter);
+      if (want > region && want <= (size_t)budget) region = want;
+    }
+    sw.lds_entries = (uint32_t)(region / 8);
+    const size_t lds = (size_t)kSpaceBytes + region;
     TUNER_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(var->fn),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     hipEvent_t ev0 = nullptr, ev1 = nullptr;

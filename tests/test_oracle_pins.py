@@ -175,6 +175,15 @@ def test_mask_count_conv_exact():
     assert int(v2.sum()) == 4096
 
 
+def test_mask_count_paper_spaces():
+    """Work-group rule wg_x * wg_y <= 1024 keeps 54 of the 64 (wg_x, wg_y) pairs."""
+    for maker in (wl.paper_convolution, wl.paper_raycasting, wl.paper_stereo):
+        w = maker()
+        n = w.space.n_configs
+        _, valid, _ = oracle.predict_range(w.space, None, 0, n, threads=8, want_yhat=False)
+        assert int(valid.sum()) == w.n_valid == n * 54 // 64
+
+
 def test_mask_count_large_analytic():
     """Digits 0..3 decide validity and are constant over aligned blocks of
     2**15 indices: count valid blocks at their first index."""

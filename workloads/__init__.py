@@ -326,14 +326,14 @@ def _paper_space(name: str, extra: List[List[float]], extra_scales: List[int],
 def paper_convolution(seed: int = 11, k: int = 200) -> Workload:
     sp = _paper_space("convolution", [[0.0, 1.0]] * 5, [SCALE_LINEAR] * 5,
                       ["image", "local", "padding", "interleave", "unroll"])
-    return Workload("paper-convolution", sp, make_model([9, 30, 1], 11, seed), k)
+    return Workload("paper-convolution", sp, make_model([9, 30, 1], 11, seed), k, n_valid=110_592)
 
 
 def paper_raycasting(seed: int = 12, k: int = 300) -> Workload:
     sp = _paper_space("raycasting", [[0.0, 1.0]] * 5 + [[1.0, 2.0, 4.0, 8.0, 16.0]],
                       [SCALE_LINEAR] * 5 + [SCALE_LOG2],
                       ["image_data", "image_tf", "local_tf", "const_tf", "interleave", "unroll"])
-    return Workload("paper-raycasting", sp, make_model([10, 30, 1], 11, seed), k)
+    return Workload("paper-raycasting", sp, make_model([10, 30, 1], 11, seed), k, n_valid=552_960)
 
 
 def paper_stereo(seed: int = 13, k: int = 300) -> Workload:
@@ -341,7 +341,7 @@ def paper_stereo(seed: int = 13, k: int = 300) -> Workload:
                       [SCALE_LINEAR] * 4 + [SCALE_LOG2] * 3,
                       ["image_l", "image_r", "local_l", "local_r", "unroll_disp",
                        "unroll_dx", "unroll_dy"])
-    return Workload("paper-stereo", sp, make_model([11, 30, 1], 11, seed), k)
+    return Workload("paper-stereo", sp, make_model([11, 30, 1], 11, seed), k, n_valid=1_990_656)
 
 
 # ---- small irregular spaces for brute-force tests --------------------------
