@@ -24,9 +24,9 @@ PEAK_FP32_MATRIX_TFLOPS = 157.3   # MI355X published dense fp32 matrix (= fp32 v
 PEAK_HBM_GBS = 8000.0
 # HBM bytes per sweep launch from rocprofv3 FETCH_SIZE / WRITE_SIZE (KiB per dispatch, scaled
 # by the factors a plain 1 GiB copy gives in the same run: 2.000 and 1.000); see
-# profiles/sweep_kernel_cfg3.md.  Not measurable from inside this script.
-TRAFFIC_BYTES = {("cfg3", "topk"): (7083.25 * 2.0 + 12330.02) * 1024.0,
-                 ("cfg3", "all"): 528392.0 * 1024.0}
+# profiles/sweep_kernel_f32mfma_cfg3.md.  Not measurable from inside this script.
+TRAFFIC_BYTES = {("cfg3", "topk", "f32-mfma"): (10173.75 * 2.0 + 23412.22) * 1024.0,
+                 ("cfg3", "all", "f32-mfma"): 525328.0 * 1024.0}
 
 
 def cpu_baseline(w, target_seconds: float = 12.0, blocks: int = 0):
@@ -149,7 +149,7 @@ def main():
         achieved = flops_per_launch / (kernel_ms * 1e-3) / 1e12
         roof = {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP32_MATRIX_TFLOPS,
                 "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MATRIX_TFLOPS,
-                "traffic": TRAFFIC_BYTES.get((args.workload, args.mode)),
+                "traffic": TRAFFIC_BYTES.get((args.workload, args.mode, args.net)),
                 "kernel": "sweep_kernel (fp32 MFMA 32x32x2)", "kernel_ms": kernel_ms,
                 "launches_per_step": launches_per_step,
                 "flop_per_config": flop_per_cfg, "evaluated_configs_per_launch": n_valid / launches_per_step,
