@@ -47,6 +47,7 @@ struct SweepParams {
   uint64_t begin, count;
   uint32_t n_chunks, n_units;  // chunks of waves*R*tile configurations; queue units of `super` chunks
   int32_t super;
+  int32_t r_used;              // tiles per wave and chunk actually used (1 .. the variant's R)
   int32_t n_members, members_per_stage, n_stages, member_words;
   int32_t mode, k;
   float inv_members;          // 1 / n_members, rounded once from double

@@ -42,7 +42,10 @@ __global__ void __launch_bounds__(NW * 64) sweep_kernel(const SweepParams prm) {
   __shared__ unsigned long long s_tau, s_tau_local;
 
   constexpr int kTile = Net::kTile;
-  constexpr int kIter = kWaves * R * kTile;   // configurations per chunk
+  // configurations per chunk: every wave takes r_used (<= R) tiles of it; small spaces
+  // use fewer tiles per wave so that their chunks still cover every compute unit
+  const int r_used = prm.r_used;
+  const uint32_t kIter = (uint32_t)(kWaves * kTile) * (uint32_t)r_used;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave_u = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave index, known uniform
   const int c = kTile == 32 ? (lane & 31) : lane, h = kTile == 32 ? (lane >> 5) : 0;
@@ -138,8 +141,9 @@ __global__ void __launch_bounds__(NW * 64) sweep_kernel(const SweepParams prm) {
 #pragma unroll
     for (int r = 0; r < R; ++r) {
       // uniform: tile start inside the range, and how many of its configurations exist
-      const uint64_t t0 = (uint64_t)chunk * kIter + (uint32_t)((wave_u * R + r) * kTile);
-      const uint32_t left = t0 < prm.count ? (uint32_t)min((uint64_t)kTile, prm.count - t0) : 0u;
+      const uint64_t t0 = (uint64_t)chunk * kIter + (uint32_t)((wave_u * r_used + r) * kTile);
+      const uint32_t left =
+          (r < r_used && t0 < prm.count) ? (uint32_t)min((uint64_t)kTile, prm.count - t0) : 0u;
       const uint32_t i = (uint32_t)(prm.begin + t0) + (uint32_t)c;   // any 32-bit index decodes safely
       idx[r] = i;
       bool v = (uint32_t)c < left;
@@ -185,8 +189,9 @@ __global__ void __launch_bounds__(NW * 64) sweep_kernel(const SweepParams prm) {
       if constexpr (kTile == 32) y = pair_sum(y);
       y = (y + bo_sum) * prm.inv_members + 0.0f;
       if (prm.mode == MODE_ALL) {
-        const uint64_t t0 = (uint64_t)chunk * kIter + (uint32_t)((wave_u * R + r) * kTile);
-        const uint32_t left = t0 < prm.count ? (uint32_t)min((uint64_t)kTile, prm.count - t0) : 0u;
+        const uint64_t t0 = (uint64_t)chunk * kIter + (uint32_t)((wave_u * r_used + r) * kTile);
+        const uint32_t left =
+            (r < r_used && t0 < prm.count) ? (uint32_t)min((uint64_t)kTile, prm.count - t0) : 0u;
         if (h == 0 && (uint32_t)c < left) {
           prm.pred[t0 + (uint32_t)c] = ok[r] ? y : __builtin_inff();
           if (prm.mask) prm.mask[t0 + (uint32_t)c] = ok[r] ? 1 : 0;

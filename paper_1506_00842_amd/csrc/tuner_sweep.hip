@@ -100,9 +100,87 @@ __global__ void __launch_bounds__(256) prep_kernel(const DevSpace sp, const Prep
 }
 
 // ---------------------------------------------------------------------------
-// Grid merge: lists of kp sorted keys, pairwise: the kp smallest of two sorted
-// lists are min(A[i], B[kp-1-i]) (a bitonic sequence), then a bitonic merge.
+// Grid merge of sorted lists of kp keys.  The kp smallest of two sorted lists
+// are min(A[i], B[kp-1-i]) (a bitonic sequence), which a bitonic merge sorts.
+//
+// merge_tree_kernel: a workgroup loads 2^levels lists (list indices base + j * stride0)
+// into LDS, merges them pairwise level by level there, and writes the result over
+// its first list; with `final` set (single workgroup) it also writes the caller's
+// outputs.  merge_kernel: one pair per workgroup, in place in global memory, for
+// lists too long for LDS.
 // ---------------------------------------------------------------------------
+struct MergeParams {
+  unsigned long long* pools;
+  unsigned long long* extra;   // list index n_pool_lists (the caller's running result)
+  uint32_t cap, n_pool_lists, n_lists, kp;
+  uint32_t stride0, levels;
+  int32_t final, k;
+  float* values;
+  uint32_t* indices;
+  int32_t* n_found;
+};
+
+__device__ __forceinline__ void emit_result(const unsigned long long* list, int i, int32_t k, float* values,
+                                            uint32_t* indices, int32_t* n_found) {
+  const unsigned long long key = list[i];
+  const bool real = key != kKeyMax;
+  values[i] = real ? unorder_bits((uint32_t)(key >> 32)) : __builtin_inff();
+  indices[i] = real ? (uint32_t)key : 0xffffffffu;
+  if (i == 0 && !real) *n_found = 0;
+  if (real && (i == k - 1 || list[i + 1] == kKeyMax)) *n_found = i + 1;
+}
+
+__global__ void __launch_bounds__(kMergeThreads) merge_tree_kernel(const MergeParams mp) {
+  extern __shared__ __align__(16) unsigned char merge_smem[];
+  unsigned long long* lds = reinterpret_cast<unsigned long long*>(merge_smem);
+  const uint32_t tid = threadIdx.x, kp = mp.kp;
+  const uint32_t slots = 1u << mp.levels;
+  const uint32_t base = blockIdx.x * mp.stride0 * slots;
+  auto list_ptr = [&](uint32_t j) -> unsigned long long* {
+    return j < mp.n_pool_lists ? mp.pools + (size_t)j * mp.cap : mp.extra;
+  };
+  for (uint32_t j = 0; j < slots; ++j) {
+    const uint32_t li = base + j * mp.stride0;
+    if (li < mp.n_lists) {
+      const unsigned long long* src = list_ptr(li);
+      for (uint32_t x = tid; x < kp; x += kMergeThreads) lds[j * kp + x] = src[x];
+    } else {
+      for (uint32_t x = tid; x < kp; x += kMergeThreads) lds[j * kp + x] = kKeyMax;
+    }
+  }
+  __syncthreads();
+  const uint32_t half = kp >> 1;
+  for (uint32_t s = 1; s < slots; s <<= 1) {
+    const uint32_t npairs = slots / (2 * s);
+    // A[i] = min(A[i], B[kp-1-i]) over every pair (A = slot 2 m s, B = slot 2 m s + s)
+    for (uint32_t t = tid; t < npairs * kp; t += kMergeThreads) {
+      const uint32_t m = t / kp, i = t - m * kp;
+      unsigned long long* A = lds + (size_t)(2 * m * s) * kp;
+      const unsigned long long a = A[i], b = A[(size_t)s * kp + (kp - 1 - i)];
+      A[i] = a < b ? a : b;
+    }
+    __syncthreads();
+    for (uint32_t j = half; j > 0; j >>= 1) {
+      for (uint32_t t = tid; t < npairs * half; t += kMergeThreads) {
+        const uint32_t m = t / half, u = t - m * half;
+        unsigned long long* A = lds + (size_t)(2 * m * s) * kp;
+        const uint32_t i = ((u & ~(j - 1)) << 1) | (u & (j - 1));
+        const uint32_t l = i | j;
+        const unsigned long long x = A[i], y = A[l];
+        if (x > y) { A[i] = y; A[l] = x; }
+      }
+      __syncthreads();
+    }
+  }
+  unsigned long long* dst = list_ptr(base);
+  for (uint32_t x = tid; x < kp; x += kMergeThreads) dst[x] = lds[x];
+  if (mp.final) {
+    // slot 0 holds kp >= k sorted keys; one more sentinel for the look-ahead at k - 1
+    for (int i = (int)tid; i < mp.k; i += kMergeThreads)
+      emit_result(lds, i, mp.k, mp.values, mp.indices, mp.n_found);
+  }
+}
+
 __global__ void __launch_bounds__(kMergeThreads)
 merge_kernel(unsigned long long* pools, uint32_t cap, unsigned long long* extra, uint32_t n_pool_lists,
              uint32_t kp, uint32_t half) {
@@ -129,14 +207,8 @@ merge_kernel(unsigned long long* pools, uint32_t cap, unsigned long long* extra,
 __global__ void __launch_bounds__(256)
 finalize_kernel(const unsigned long long* list, int32_t k, float* values, uint32_t* indices,
                 int32_t* n_found) {
-  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < k; i += gridDim.x * blockDim.x) {
-    const unsigned long long key = list[i];
-    const bool real = key != kKeyMax;
-    values[i] = real ? unorder_bits((uint32_t)(key >> 32)) : __builtin_inff();
-    indices[i] = real ? (uint32_t)key : 0xffffffffu;
-    if (i == 0 && !real) *n_found = 0;
-    if (real && (i == k - 1 || list[i + 1] == kKeyMax)) *n_found = i + 1;
-  }
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < k; i += gridDim.x * blockDim.x)
+    emit_result(list, i, k, values, indices, n_found);
 }
 
 // ---------------------------------------------------------------------------
@@ -302,11 +374,25 @@ static int run_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin
   hipLaunchKernelGGL(prep_kernel, dim3(prep_blocks), dim3(256), 0, stream, sp->dev, pp);
   TUNER_HIP_TRY(hipGetLastError());
 
-  const int iter = var->waves * var->R * var->tile;
-  const uint64_t n_chunks64 = (count + iter - 1) / iter;
-  const uint32_t n_chunks = (uint32_t)n_chunks64;   // count <= 2^32, iter >= 512
   const int n_cu = di.n_cu > 0 ? di.n_cu : 1;
   const uint32_t max_groups = (uint32_t)std::min(n_cu, kMaxGroups);
+  // tiles per wave and chunk: the variant's R, or fewer when the range is so short that
+  // smaller chunks finish sooner (rounds of chunks over the workgroups x tiles per chunk)
+  int r_used = var->R;
+  {
+    uint64_t best = ~0ull;
+    const uint64_t full = (uint64_t)var->waves * var->R * var->tile;
+    const bool is_short = (count + full - 1) / full < 8ull * max_groups;
+    for (int r = var->R; r >= (is_short ? 1 : var->R); --r) {
+      const uint64_t it = (uint64_t)var->waves * r * var->tile;
+      const uint64_t chunks = (count + it - 1) / it;
+      const uint64_t cost = (chunks + max_groups - 1) / max_groups * (uint64_t)r;
+      if (cost < best) { best = cost; r_used = r; }
+    }
+  }
+  const int iter = var->waves * r_used * var->tile;
+  const uint64_t n_chunks64 = (count + iter - 1) / iter;
+  const uint32_t n_chunks = (uint32_t)n_chunks64;   // count <= 2^32, iter >= 256
   // queue unit: up to kMaxSuper chunks, while every workgroup still gets >= 8 units
   uint32_t super = 1;
   while (super < (uint32_t)kMaxSuper && n_chunks64 / (2 * super) >= 8ull * max_groups) super *= 2;
@@ -325,6 +411,7 @@ static int run_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin
     sw.n_chunks = n_chunks;
     sw.n_units = n_units;
     sw.super = (int32_t)super;
+    sw.r_used = r_used;
     sw.n_members = sh.E;
     sw.members_per_stage = mps;
     sw.n_stages = (sh.E + mps - 1) / mps;
@@ -369,18 +456,57 @@ static int run_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin
 
   if (mode == MODE_TOPK) {
     // lists: pool 0..groups-1, then the running result
-    uint32_t n = groups + 1;
-    while (n > 1) {
-      const uint32_t half = (n + 1) / 2;
-      hipLaunchKernelGGL(merge_kernel, dim3(n - half), dim3(kMergeThreads), 0, stream, pools, L.cap, extra,
-                         groups, L.kp, half);
-      TUNER_HIP_TRY(hipGetLastError());
-      n = half;
+    const uint32_t n_lists = groups + 1;
+    const size_t list_bytes = (size_t)L.kp * 8;
+    const size_t merge_lds_max = std::min<size_t>((size_t)di.max_lds, 128u << 10);
+    bool finalized = false;
+    if (2 * list_bytes <= merge_lds_max) {
+      // in LDS, up to 16 lists per workgroup and launch
+      uint32_t max_levels = 0;
+      while (max_levels < 4 && (list_bytes << (max_levels + 1)) <= merge_lds_max) ++max_levels;
+      TUNER_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(merge_tree_kernel),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)merge_lds_max));
+      uint32_t live = n_lists, stride = 1;
+      while (live > 1) {
+        uint32_t levels = 1;
+        while (levels < max_levels && (1u << levels) < live) ++levels;
+        const uint32_t blocks = (live + (1u << levels) - 1) >> levels;
+        MergeParams mp{};
+        mp.pools = pools;
+        mp.extra = extra;
+        mp.cap = L.cap;
+        mp.n_pool_lists = groups;
+        mp.n_lists = n_lists;
+        mp.kp = L.kp;
+        mp.stride0 = stride;
+        mp.levels = levels;
+        mp.final = blocks == 1 ? 1 : 0;
+        mp.k = k;
+        mp.values = values;
+        mp.indices = indices;
+        mp.n_found = n_found;
+        hipLaunchKernelGGL(merge_tree_kernel, dim3(blocks), dim3(kMergeThreads), list_bytes << levels, stream, mp);
+        TUNER_HIP_TRY(hipGetLastError());
+        finalized = blocks == 1;
+        live = blocks;
+        stride <<= levels;
+      }
+    } else {
+      uint32_t n = n_lists;
+      while (n > 1) {
+        const uint32_t half = (n + 1) / 2;
+        hipLaunchKernelGGL(merge_kernel, dim3(n - half), dim3(kMergeThreads), 0, stream, pools, L.cap, extra,
+                           groups, L.kp, half);
+        TUNER_HIP_TRY(hipGetLastError());
+        n = half;
+      }
     }
-    const unsigned long long* list0 = groups > 0 ? pools : extra;
-    hipLaunchKernelGGL(finalize_kernel, dim3((k + 255) / 256), dim3(256), 0, stream, list0, k, values,
-                       indices, n_found);
-    TUNER_HIP_TRY(hipGetLastError());
+    if (!finalized) {
+      const unsigned long long* list0 = groups > 0 ? pools : extra;
+      hipLaunchKernelGGL(finalize_kernel, dim3((k + 255) / 256), dim3(256), 0, stream, list0, k, values,
+                         indices, n_found);
+      TUNER_HIP_TRY(hipGetLastError());
+    }
   }
   return TUNER_OK;
 }
