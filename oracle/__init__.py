@@ -28,6 +28,9 @@ def lib():
             build()
         L = C.CDLL(LIB_PATH)
         L.oracle_select_topk.restype = C.c_int64
+        L.oracle_sample_valid.restype = C.c_int64
+        L.oracle_mean_relative_error.restype = C.c_double
+        L.oracle_best_of.restype = C.c_int64
         _lib = L
     return _lib
 
@@ -122,3 +125,49 @@ def select_topk(yhat, valid, index_base: int, k: int):
 def topk(space, model, begin: int, count: int, k: int, threads: int = 1):
     yhat, valid, _ = predict_range(space, model, begin, count, threads)
     return select_topk(yhat, valid, begin, k)
+
+
+def sample_valid(space, seed: int, n_samples: int, max_draws: int) -> np.ndarray:
+    """First n_samples distinct valid indices in draw order (uint64)."""
+    keep, a = _space_args(space)
+    out = np.empty(max(n_samples, 1), np.uint64)
+    n = lib().oracle_sample_valid(a[0], a[1], a[4], a[5], a[6], C.c_uint64(seed & (2 ** 64 - 1)),
+                                  C.c_int64(n_samples), C.c_uint64(max_draws), _p(out, C.c_uint64))
+    return out[:n].copy()
+
+
+def train_ensemble(space, n_members: int, hidden: int, indices, times, parts, initial_weights,
+                   epochs: int, learning_rate: float, momentum: float):
+    """Returns (weights fp32[E * per], loss float64[E, epochs + 1])."""
+    keep, a = _space_args(space)
+    idx = np.ascontiguousarray(indices, dtype=np.uint64)
+    t = np.ascontiguousarray(times, dtype=np.float32)
+    pt = np.ascontiguousarray(parts, dtype=np.int32)
+    w0 = np.ascontiguousarray(initial_weights, dtype=np.float32)
+    P = len(keep[0])
+    per = hidden * P + hidden + hidden + 1
+    assert len(w0) == n_members * per and len(t) == len(idx) == len(pt)
+    w = np.empty_like(w0)
+    loss = np.empty((n_members, epochs + 1), np.float64)
+    lib().oracle_train_ensemble(*a, C.c_int(n_members), C.c_int(hidden), C.c_int64(len(idx)),
+                                _p(idx, C.c_uint64), _p(t, C.c_float), _p(pt, C.c_int32),
+                                _p(w0, C.c_float), C.c_int(epochs), C.c_float(learning_rate),
+                                C.c_float(momentum), _p(w, C.c_float), _p(loss, C.c_double))
+    return w, loss
+
+
+def mean_relative_error(predictions, times):
+    """(mean of |exp(prediction) - t| / t over usable entries, count)."""
+    p = np.ascontiguousarray(predictions, dtype=np.float32)
+    t = np.ascontiguousarray(times, dtype=np.float32)
+    n = C.c_int64(0)
+    m = lib().oracle_mean_relative_error(C.c_int64(len(p)), _p(p, C.c_float), _p(t, C.c_float), C.byref(n))
+    return float(m), int(n.value)
+
+
+def best_of(times):
+    """(position of the lowest usable time or -1, that time)."""
+    t = np.ascontiguousarray(times, dtype=np.float32)
+    bt = C.c_float(0)
+    pos = lib().oracle_best_of(C.c_int64(len(t)), _p(t, C.c_float), C.byref(bt))
+    return int(pos), float(bt.value)

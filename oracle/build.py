@@ -5,13 +5,13 @@ import os
 import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-SRC = os.path.join(HERE, "tuner_oracle.cpp")
+SOURCES = [os.path.join(HERE, f) for f in ("tuner_oracle.cpp", "train_oracle.cpp")]
 LIB_PATH = os.path.join(HERE, "liboracle.so")
 
 
 def build(verbose: bool = False) -> str:
     cmd = ["g++", "-O2", "-std=c++17", "-fPIC", "-shared", "-pthread",
-           "-ffp-contract=off", "-o", LIB_PATH, SRC]
+           "-ffp-contract=off", "-o", LIB_PATH, *SOURCES]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
