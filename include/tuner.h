@@ -190,6 +190,105 @@ int tuner_decode_range(const tuner_space* space, uint64_t index_begin, uint64_t 
                        void* hip_stream);
 
 /*
+ * Ensemble evaluation at an arbitrary list of configurations (the held-out
+ * configurations of Section 6, first paragraph; the training samples of
+ * Section 5.2): same arithmetic as tuner_predict_all, with configuration
+ * indices read from a list instead of a range.
+ *   indices_dev      DEVICE, n uint32 configuration indices (each < N; an index
+ *                    outside the space is not detected)
+ *   predictions_dev  DEVICE, n floats; +INF where the configuration is invalid
+ *   valid_mask_dev   DEVICE, optional, n bytes 0/1
+ * Workspace as for tuner_predict_all (tuner_workspace_bytes with k = 0).
+ */
+int tuner_predict_indices(const tuner_space* space, const tuner_model* model, uint64_t n,
+                          const uint32_t* indices_dev, float* predictions_dev,
+                          uint8_t* valid_mask_dev, void* workspace_dev, size_t workspace_bytes,
+                          void* hip_stream);
+
+/*
+ * Random choice of training configurations (Section 5.2: the benchmarks are
+ * run "on several randomly chosen parameter configurations"; invalid ones are
+ * ignored).  Draw c = 0, 1, 2, ... is the configuration index
+ *     floor(z_c * N / 2^64),  z_c = splitmix64 output function of seed + (c + 1) * 0x9E3779B97F4A7C15
+ * and the sample is the first n_samples DISTINCT, statically VALID indices in
+ * draw order among draws 0 .. max_draws - 1 (sampling without replacement).
+ *   indices_dev   DEVICE out, n_samples uint32 (entries past *n_found_dev are 0xFFFFFFFF)
+ *   n_found_dev   DEVICE out, one int32 = number of indices written (< n_samples
+ *                 only if max_draws draws did not yield enough)
+ *   workspace     DEVICE, >= tuner_sample_workspace_bytes(max_draws), 256-byte aligned
+ * Errors: EINVAL (null, n_samples < 1, max_draws < n_samples), ETOOLARGE
+ * (max_draws > 2^24), EWORKSPACE, EHIP.
+ */
+size_t tuner_sample_workspace_bytes(uint64_t max_draws);
+int tuner_sample_valid(const tuner_space* space, uint64_t seed, uint32_t n_samples,
+                       uint64_t max_draws, uint32_t* indices_dev, int32_t* n_found_dev,
+                       void* workspace_dev, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Training of the bagged ensemble (Section 5.2): E networks P -> hidden -> 1
+ * (sigmoid hidden units, linear output); the training data is split into E
+ * parts and network e is trained on all the data except part e; the target is
+ * the natural logarithm of the measured execution time and the loss of network
+ * e is the mean squared error over its training samples,
+ *     L_e = 1/n_e * sum_s (y_e(x_s) - ln t_s)^2.
+ * The paper names no training algorithm; this library uses full-batch gradient
+ * descent with momentum from caller-supplied initial weights:
+ *     v <- momentum * v - learning_rate * dL_e/dw,   w <- w + v,   v_0 = 0,
+ * for a fixed number of epochs, in fp32.  A sample is ignored (Section 5.2,
+ * last paragraph) when its configuration is statically invalid or its time is
+ * not a finite number > 0 (a failed run).
+ *   sample_indices_dev   DEVICE, n_samples uint32 configuration indices
+ *   sample_times_dev     DEVICE, n_samples floats, measured execution times
+ *   sample_parts_dev     DEVICE, n_samples int32; network e skips samples with part == e
+ *   initial_weights_dev  DEVICE, E x (hidden * P + hidden + hidden + 1) floats, layout of
+ *                        tuner_model.weights_dev (W1[hidden][P], b1, w_o, b_o per network)
+ *   weights_out_dev      DEVICE out, same size (may alias initial_weights_dev)
+ *   loss_history_dev     DEVICE out, optional, [E][epochs + 1] floats: L_e before each
+ *                        update, and last the loss of the final weights
+ * A network with no usable training sample keeps its initial weights (loss 0).
+ * Limits: 1 <= hidden <= 64, n_samples <= 2^24, epochs >= 0.
+ * Workspace: >= tuner_train_workspace_bytes(space, n_samples), 256-byte aligned.
+ */
+typedef struct {
+  int32_t epochs;
+  float learning_rate;
+  float momentum;
+} tuner_train_options;
+
+size_t tuner_train_workspace_bytes(const tuner_space* space, uint64_t n_samples);
+int tuner_train_ensemble(const tuner_space* space, int32_t n_members, int32_t hidden,
+                         uint64_t n_samples, const uint32_t* sample_indices_dev,
+                         const float* sample_times_dev, const int32_t* sample_parts_dev,
+                         const float* initial_weights_dev, const tuner_train_options* options,
+                         float* weights_out_dev, float* loss_history_dev, void* workspace_dev,
+                         size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Model accuracy as the paper reports it (Section 6, first paragraph): the mean
+ * relative error |exp(prediction) - t| / t over configurations that were not
+ * used for training, invalid configurations and failed runs (time not a finite
+ * number > 0) left out.  Predictions are log-times (natural logarithm).
+ *   predictions_dev  DEVICE, n floats (as written by tuner_predict_indices)
+ *   times_dev        DEVICE, n floats, measured times
+ *   mean_error_dev   DEVICE out, one float (0 if no configuration counts)
+ *   n_used_dev       DEVICE out, one int32
+ */
+int tuner_mean_relative_error(uint64_t n, const float* predictions_dev, const float* times_dev,
+                              float* mean_error_dev, int32_t* n_used_dev, void* hip_stream);
+
+/*
+ * Second stage of the tuner (Section 5.3, third paragraph): among the M
+ * candidates whose execution times were measured, the one with the lowest
+ * time; ties go to the earlier entry; failed runs (time not a finite number
+ * > 0) are skipped.
+ *   best_pos_dev   DEVICE out, one int32: position in the list, -1 if every
+ *                  candidate failed (the tuner then returns nothing)
+ *   best_time_dev  DEVICE out, one float (+INF if none)
+ */
+int tuner_best_of(uint64_t m, const float* times_dev, int32_t* best_pos_dev, float* best_time_dev,
+                  void* hip_stream);
+
+/*
  * Timing of the dominant kernel (the fused sweep) for roofline reports.  While
  * enabled, every predict call brackets its sweep kernel with a pair of HIP
  * events on the caller's stream.  tuner_profile_read waits for the recorded

@@ -29,6 +29,9 @@ EXPORTS = [
     "tuner_space_encode", "tuner_space_decode_device_arith", "tuner_workspace_bytes",
     "tuner_predict_topk", "tuner_predict_all", "tuner_decode_range", "tuner_last_error",
     "tuner_version", "tuner_profile_enable", "tuner_profile_read",
+    "tuner_predict_indices", "tuner_sample_workspace_bytes", "tuner_sample_valid",
+    "tuner_train_workspace_bytes", "tuner_train_ensemble", "tuner_mean_relative_error",
+    "tuner_best_of",
 ]
 
 
@@ -36,6 +39,10 @@ class TunerError(RuntimeError):
     def __init__(self, code: int, msg: str):
         super().__init__(f"tuner error {code}: {msg}")
         self.code = code
+
+
+class _TrainOptions(C.Structure):
+    _fields_ = [("epochs", C.c_int32), ("learning_rate", C.c_float), ("momentum", C.c_float)]
 
 
 class _Model(C.Structure):
@@ -82,6 +89,20 @@ def load_library():
                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
     L.tuner_decode_range.argtypes = [C.c_void_p, C.c_uint64, C.c_uint64, C.c_void_p, C.c_void_p,
                                      C.c_void_p, C.c_void_p]
+    L.tuner_predict_indices.argtypes = [C.c_void_p, C.POINTER(_Model), C.c_uint64, C.c_void_p,
+                                        C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    L.tuner_sample_workspace_bytes.restype = C.c_size_t
+    L.tuner_sample_workspace_bytes.argtypes = [C.c_uint64]
+    L.tuner_sample_valid.argtypes = [C.c_void_p, C.c_uint64, C.c_uint32, C.c_uint64, C.c_void_p,
+                                     C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    L.tuner_train_workspace_bytes.restype = C.c_size_t
+    L.tuner_train_workspace_bytes.argtypes = [C.c_void_p, C.c_uint64]
+    L.tuner_train_ensemble.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_uint64, C.c_void_p,
+                                       C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(_TrainOptions),
+                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    L.tuner_mean_relative_error.argtypes = [C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p,
+                                            C.c_void_p, C.c_void_p]
+    L.tuner_best_of.argtypes = [C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     _lib = L
     return L
 
@@ -222,3 +243,57 @@ def tuner_decode_range(space, index_begin, index_count, digits_dev, features_dev
     _check(load_library().tuner_decode_range(
         space.ptr, int(index_begin), int(index_count), _dp(digits_dev), _dp(features_dev),
         _dp(valid_mask_dev), _stream(stream)))
+
+
+def _nbytes(t):
+    return t.numel() * t.element_size() if t is not None else 0
+
+
+def tuner_predict_indices(space, model, n, indices_dev, predictions_dev, valid_mask_dev,
+                          workspace_dev, stream=None):
+    _check(load_library().tuner_predict_indices(
+        space.ptr, C.byref(model.c), int(n), _dp(indices_dev), _dp(predictions_dev),
+        _dp(valid_mask_dev), _dp(workspace_dev), _nbytes(workspace_dev), _stream(stream)))
+
+
+def tuner_sample_workspace_bytes(max_draws: int) -> int:
+    n = load_library().tuner_sample_workspace_bytes(int(max_draws))
+    if n == 0:
+        raise TunerError(TUNER_ETOOLARGE, tuner_last_error())
+    return int(n)
+
+
+def tuner_sample_valid(space, seed, n_samples, max_draws, indices_dev, n_found_dev, workspace_dev,
+                       stream=None):
+    _check(load_library().tuner_sample_valid(
+        space.ptr, int(seed) & (2 ** 64 - 1), int(n_samples), int(max_draws), _dp(indices_dev),
+        _dp(n_found_dev), _dp(workspace_dev), _nbytes(workspace_dev), _stream(stream)))
+
+
+def tuner_train_workspace_bytes(space, n_samples: int) -> int:
+    n = load_library().tuner_train_workspace_bytes(space.ptr, int(n_samples))
+    if n == 0:
+        raise TunerError(TUNER_ETOOLARGE, tuner_last_error())
+    return int(n)
+
+
+def tuner_train_ensemble(space, n_members, hidden, n_samples, sample_indices_dev, sample_times_dev,
+                         sample_parts_dev, initial_weights_dev, epochs, learning_rate, momentum,
+                         weights_out_dev, loss_history_dev, workspace_dev, stream=None):
+    opt = _TrainOptions(int(epochs), float(learning_rate), float(momentum))
+    _check(load_library().tuner_train_ensemble(
+        space.ptr, int(n_members), int(hidden), int(n_samples), _dp(sample_indices_dev),
+        _dp(sample_times_dev), _dp(sample_parts_dev), _dp(initial_weights_dev), C.byref(opt),
+        _dp(weights_out_dev), _dp(loss_history_dev), _dp(workspace_dev), _nbytes(workspace_dev),
+        _stream(stream)))
+
+
+def tuner_mean_relative_error(n, predictions_dev, times_dev, mean_error_dev, n_used_dev, stream=None):
+    _check(load_library().tuner_mean_relative_error(
+        int(n), _dp(predictions_dev), _dp(times_dev), _dp(mean_error_dev), _dp(n_used_dev),
+        _stream(stream)))
+
+
+def tuner_best_of(m, times_dev, best_pos_dev, best_time_dev, stream=None):
+    _check(load_library().tuner_best_of(int(m), _dp(times_dev), _dp(best_pos_dev), _dp(best_time_dev),
+                                        _stream(stream)))

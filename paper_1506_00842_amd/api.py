@@ -5,8 +5,11 @@ from __future__ import annotations
 import numpy as np
 import torch
 
-from . import (ModelHandle, TUNER_ALGO_AUTO, TUNER_FP32, tuner_decode_range, tuner_predict_all,
-               tuner_predict_topk, tuner_space_create, tuner_space_size, tuner_workspace_bytes)
+from . import (ModelHandle, TUNER_ALGO_AUTO, TUNER_FP32, tuner_best_of, tuner_decode_range,
+               tuner_mean_relative_error, tuner_predict_all, tuner_predict_indices,
+               tuner_predict_topk, tuner_sample_valid, tuner_sample_workspace_bytes,
+               tuner_space_create, tuner_space_size, tuner_train_ensemble,
+               tuner_train_workspace_bytes, tuner_workspace_bytes)
 
 
 class Sweep:
@@ -64,3 +67,71 @@ class Sweep:
         valid = torch.empty(count, dtype=torch.uint8, device=self.device)
         tuner_decode_range(self.space, begin, count, digits, feats, valid)
         return digits, feats, valid
+
+    def predict_indices(self, indices, want_mask: bool = True, stream=None):
+        """indices: int32/uint32-bit tensor on the device -> (predictions f32[n], mask u8[n] or None)."""
+        n = indices.numel()
+        out = torch.empty(n, dtype=torch.float32, device=self.device)
+        mask = torch.empty(n, dtype=torch.uint8, device=self.device) if want_mask else None
+        tuner_predict_indices(self.space, self.model, n, indices, out, mask, self.workspace, stream)
+        return out, mask
+
+
+def _as_index_tensor(indices, device):
+    """uint32 configuration indices kept in an int32 tensor (same bytes)."""
+    if isinstance(indices, torch.Tensor):
+        return indices.to(device)
+    a = np.ascontiguousarray(indices).astype(np.uint32).view(np.int32)
+    return torch.from_numpy(a).to(device)
+
+
+class Tuner:
+    """The stages around the sweep for one space: sampling, training, metrics
+    (device buffers from PyTorch; every computation in the library)."""
+
+    def __init__(self, space, device: str = "cuda:0"):
+        self.device = torch.device(device)
+        self.space_desc = space
+        self.space = tuner_space_create(space.radices, space.flat_values, space.scales,
+                                        space.constraint_terms, space.constraint_bounds)
+        self.n_params = len(space.radices)
+
+    def sample_valid(self, seed: int, n_samples: int, max_draws: int, stream=None):
+        """-> (indices int32-tensor[n_samples] holding uint32 bits, n_found int32[1]), on the device."""
+        ws = torch.empty(tuner_sample_workspace_bytes(max_draws), dtype=torch.uint8, device=self.device)
+        out = torch.empty(n_samples, dtype=torch.int32, device=self.device)
+        found = torch.zeros(1, dtype=torch.int32, device=self.device)
+        tuner_sample_valid(self.space, seed, n_samples, max_draws, out, found, ws, stream)
+        self._keep = ws
+        return out, found
+
+    def train(self, n_members: int, hidden: int, indices, times, parts, initial_weights,
+              epochs: int, learning_rate: float, momentum: float, want_loss: bool = True, stream=None):
+        """-> (weights f32[E * per], loss f32[E, epochs + 1] or None), on the device."""
+        idx = _as_index_tensor(indices, self.device)
+        n = idx.numel()
+        t = torch.as_tensor(np.ascontiguousarray(times, dtype=np.float32)).to(self.device) \
+            if not isinstance(times, torch.Tensor) else times.to(self.device)
+        pt = torch.as_tensor(np.ascontiguousarray(parts, dtype=np.int32)).to(self.device) \
+            if not isinstance(parts, torch.Tensor) else parts.to(self.device)
+        w0 = torch.as_tensor(np.ascontiguousarray(initial_weights, dtype=np.float32)).to(self.device) \
+            if not isinstance(initial_weights, torch.Tensor) else initial_weights.to(self.device)
+        ws = torch.empty(tuner_train_workspace_bytes(self.space, n), dtype=torch.uint8, device=self.device)
+        w = torch.empty_like(w0)
+        loss = torch.zeros((n_members, epochs + 1), dtype=torch.float32, device=self.device) if want_loss else None
+        tuner_train_ensemble(self.space, n_members, hidden, n, idx, t, pt, w0, epochs, learning_rate,
+                             momentum, w, loss, ws, stream)
+        self._keep = (ws, idx, t, pt, w0)
+        return w, loss
+
+    def mean_relative_error(self, predictions, times, stream=None):
+        m = torch.zeros(1, dtype=torch.float32, device=self.device)
+        n = torch.zeros(1, dtype=torch.int32, device=self.device)
+        tuner_mean_relative_error(predictions.numel(), predictions, times, m, n, stream)
+        return m, n
+
+    def best_of(self, times, stream=None):
+        pos = torch.zeros(1, dtype=torch.int32, device=self.device)
+        bt = torch.zeros(1, dtype=torch.float32, device=self.device)
+        tuner_best_of(times.numel(), times, pos, bt, stream)
+        return pos, bt

@@ -56,6 +56,7 @@ struct SweepParams {
   NetOffsets off;
   const DevSpace* space;      // in the workspace
   const uint32_t* packed;
+  const uint32_t* index_list;  // optional: configuration t of the "range" is index_list[t]
   WsHeader* hdr;
   unsigned long long* pools;
   float* pred;

@@ -16,20 +16,10 @@
 //        -> the lane's share of the member's output (both halves of a lane pair
 //           (lane, lane ^ 32) are summed by the caller)
 #pragma once
+#include "lane_ops.h"
 #include "sweep_common.h"
 
 namespace tuner {
-
-// x[lane] + x[lane ^ 32] in every lane (v_permlane32_swap exchanges the upper 32 lanes
-// of its first operand with the lower 32 lanes of its second)
-__device__ __forceinline__ float pair_sum(float x) {
-  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
-}
-__device__ __forceinline__ int pair_sum(int x) {
-  const auto r = __builtin_amdgcn_permlane32_swap((unsigned)x, (unsigned)x, false, false);
-  return (int)(r[0] + r[1]);
-}
 
 template <class Net, int R, int NW>
 __global__ void __launch_bounds__(NW * 64) sweep_kernel(const SweepParams prm) {
@@ -144,7 +134,8 @@ __global__ void __launch_bounds__(NW * 64) sweep_kernel(const SweepParams prm) {
       const uint64_t t0 = (uint64_t)chunk * kIter + (uint32_t)((wave_u * r_used + r) * kTile);
       const uint32_t left =
           (r < r_used && t0 < prm.count) ? (uint32_t)min((uint64_t)kTile, prm.count - t0) : 0u;
-      const uint32_t i = (uint32_t)(prm.begin + t0) + (uint32_t)c;   // any 32-bit index decodes safely
+      uint32_t i = (uint32_t)(prm.begin + t0) + (uint32_t)c;   // any 32-bit index decodes safely
+      if (prm.index_list) i = (uint32_t)c < left ? prm.index_list[t0 + (uint32_t)c] : 0u;
       idx[r] = i;
       bool v = (uint32_t)c < left;
       for (int cc = 0; cc < n_constraints; ++cc) {

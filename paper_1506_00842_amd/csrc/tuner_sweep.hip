@@ -334,14 +334,18 @@ static int device_info(DeviceInfo* out) {
 
 static int run_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin, uint64_t count,
                      int mode, int k, int merge, float* values, uint32_t* indices, int32_t* n_found,
-                     float* pred, uint8_t* mask, void* ws, size_t ws_bytes, hipStream_t stream) {
+                     float* pred, uint8_t* mask, void* ws, size_t ws_bytes, hipStream_t stream,
+                     const uint32_t* index_list = nullptr) {
   Shape sh{};
   int rc = make_shape(sp, m, &sh);
   if (rc) return rc;
   const Variant* var = find_variant(sh);
   if (!var) return set_error(TUNER_ETOOLARGE, "no kernel variant for this model shape");
-  if (begin > sp->n_configs || count > sp->n_configs - begin)
+  if (index_list) {
+    if (count > (1ull << 32)) return set_error(TUNER_ETOOLARGE, "more than 2^32 list entries");
+  } else if (begin > sp->n_configs || count > sp->n_configs - begin) {
     return set_error(TUNER_EINVAL, "range outside the space");
+  }
   const Layout L = make_layout(sh, k);
   if (!ws || ws_bytes < L.total) return set_error(TUNER_EWORKSPACE, "workspace missing or too small");
   if ((reinterpret_cast<uintptr_t>(ws) & 255) != 0) return set_error(TUNER_EWORKSPACE, "workspace not 256-byte aligned");
@@ -424,6 +428,7 @@ static int run_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin
     sw.kp = L.kp;
     sw.space = space_dev;
     sw.packed = packed;
+    sw.index_list = index_list;
     sw.hdr = hdr;
     sw.pools = pools;
     sw.pred = pred;
@@ -570,6 +575,17 @@ int tuner_predict_all(const tuner_space* space, const tuner_model* model, uint64
   return tuner::run_sweep(space, model, index_begin, index_count, tuner::MODE_ALL, 0, 0, nullptr,
                           nullptr, nullptr, predictions_dev, valid_mask_dev, workspace_dev,
                           workspace_bytes, (hipStream_t)hip_stream);
+}
+
+int tuner_predict_indices(const tuner_space* space, const tuner_model* model, uint64_t n,
+                          const uint32_t* indices_dev, float* predictions_dev, uint8_t* valid_mask_dev,
+                          void* workspace_dev, size_t workspace_bytes, void* hip_stream) {
+  if (!space || !model || !predictions_dev || (n > 0 && !indices_dev))
+    return set_error(TUNER_EINVAL, "null argument");
+  if (n == 0) return TUNER_OK;
+  return tuner::run_sweep(space, model, 0, n, tuner::MODE_ALL, 0, 0, nullptr, nullptr, nullptr,
+                          predictions_dev, valid_mask_dev, workspace_dev, workspace_bytes,
+                          (hipStream_t)hip_stream, indices_dev);
 }
 
 }  // extern "C"
