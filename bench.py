@@ -63,8 +63,99 @@ def cpu_baseline(w, target_seconds: float = 12.0, blocks: int = 0):
             "evaluated_per_s": evaluated / dt}
 
 
+PEAK_FP32_VECTOR_FMA_TFLOPS = 78.6   # 256 CUs x 4 SIMDs x 16 lanes x 1 FMA x 2.4 GHz (no packed fp32)
+
+
+def bench_train(args):
+    """Training stage: one step = one whole training run of the paper-shaped ensemble
+    (Section 5.2: 11 networks of 30 sigmoid units, each trained on 10/11 of 2000 sampled
+    configurations of the convolution space) for --epochs full-batch epochs."""
+    import numpy as np
+    import torch
+    import workloads as wl
+    import paper_1506_00842_amd as T
+    from paper_1506_00842_amd.api import Tuner
+    from workloads.synthetic_benchmark import SyntheticBenchmark, initial_weights, parts_round_robin
+
+    w = wl.paper_convolution()
+    sp = w.space
+    P, E, H, n, epochs = sp.n_params, 11, 30, args.samples, args.epochs
+    eta, mu = 0.125, 0.875
+    tn = Tuner(sp)
+    idx_dev, found = tn.sample_valid(2015, n, 16 * n)
+    assert int(found.item()) == n
+    idx = idx_dev.cpu().numpy().view(np.uint32).astype(np.uint64)
+    t = SyntheticBenchmark(sp, 2015).times(idx)
+    parts = parts_round_robin(n, E)
+    w0 = initial_weights(E, P, H, 2016)
+    t_dev = torch.from_numpy(t).cuda()
+    p_dev = torch.from_numpy(parts).cuda()
+    w0_dev = torch.from_numpy(w0).cuda()
+    w_dev = torch.empty_like(w0_dev)
+    loss = torch.zeros((E, epochs + 1), dtype=torch.float32, device="cuda")
+    ws = torch.empty(T.tuner_train_workspace_bytes(tn.space, n), dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    def step():
+        T.tuner_train_ensemble(tn.space, E, H, n, idx_dev, t_dev, p_dev, w0_dev, epochs, eta, mu,
+                               w_dev, loss, ws, stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    T.tuner_profile_enable(True)
+    T.tuner_profile_read_train()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    train_ms, n_launch = T.tuner_profile_read_train()
+    T.tuner_profile_enable(False)
+    usable = (t > 0) & np.isfinite(t)
+    # (network, sample) pairs a network trains on per epoch; loss evaluation of the final
+    # weights is one more forward pass and is not counted
+    pairs = int(sum(np.sum(usable & (parts != e)) for e in range(E)))
+    # forward 2PH + 2H, backward 2PH + 7H (output error, both weight gradients, sigmoid derivative)
+    flop_per_pair = 4 * P * H + 9 * H
+    kernel_ms = train_ms / max(n_launch, 1)
+    achieved = pairs * epochs * flop_per_pair / (kernel_ms * 1e-3) / 1e12
+    l = loss.cpu().numpy()
+    out = {
+        "metric": "training sample-gradient evaluations per second (forward + backward + momentum update, "
+                  "full-batch, 11 networks)",
+        "value": pairs * epochs / (dt / args.steps), "unit": "sample-gradients/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": 1e3 * dt / args.steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "paper-convolution training", "n_samples": n, "usable_samples": int(usable.sum()),
+                   "members": E, "hidden": H, "epochs": epochs, "learning_rate": eta, "momentum": mu,
+                   "loss_first": float(l[:, 0].mean()), "loss_last": float(l[:, -1].mean()),
+                   "us_per_epoch": 1e3 * kernel_ms / epochs},
+        "roofline": {"bound": "alu", "achieved": achieved, "peak": PEAK_FP32_VECTOR_FMA_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / PEAK_FP32_VECTOR_FMA_TFLOPS, "traffic": None,
+                     "kernel": "train_kernel (one workgroup per network)", "kernel_ms": kernel_ms,
+                     "flop_per_sample_gradient": flop_per_pair,
+                     "note": "E workgroups on 256 compute units: each epoch is a dependent step, the kernel is "
+                             "latency-bound by design"},
+    }
+    if not args.no_cpu:
+        import oracle
+        ep_cpu = max(1, min(epochs, args.cpu_epochs))
+        t1 = time.perf_counter()
+        oracle.train_ensemble(sp, E, H, idx, t, parts, w0, ep_cpu, eta, mu)
+        d1 = time.perf_counter() - t1
+        out["cpu_baseline"] = {"value": pairs * ep_cpu / d1, "unit": "sample-gradients/s", "cores": 1,
+                               "kind": "oracle", "sample": f"the same training data, {ep_cpu} epochs ({d1:.1f} s)"}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
+    ap.add_argument("--stage", default="sweep", choices=["sweep", "train"],
+                    help="sweep: the full-space model sweep (headline); train: ensemble training")
+    ap.add_argument("--samples", type=int, default=2000, help="training configurations (train stage)")
+    ap.add_argument("--epochs", type=int, default=1000, help="epochs per training run (train stage)")
+    ap.add_argument("--cpu-epochs", type=int, default=1000, help="epochs of the CPU oracle baseline (train stage)")
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
@@ -86,6 +177,8 @@ def main():
         print("bench.py: this build runs on ONE GPU (the sweep shards by index range; "
               "no multi-GPU path is built). Use --gpus 1.", file=sys.stderr)
         sys.exit(2)
+    if args.stage == "train":
+        return bench_train(args)
 
     import torch
     import workloads as wl

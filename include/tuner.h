@@ -289,14 +289,17 @@ int tuner_best_of(uint64_t m, const float* times_dev, int32_t* best_pos_dev, flo
                   void* hip_stream);
 
 /*
- * Timing of the dominant kernel (the fused sweep) for roofline reports.  While
- * enabled, every predict call brackets its sweep kernel with a pair of HIP
- * events on the caller's stream.  tuner_profile_read waits for the recorded
- * events, returns the summed kernel time in milliseconds and the number of
- * launches, and forgets them.  Process-wide, not thread-safe; off by default.
+ * Timing of the dominant kernels (the fused sweep of Section 5.3; the training
+ * kernel of Section 5.2) for roofline reports.  While enabled, every predict
+ * call brackets its sweep kernel, and every tuner_train_ensemble call its
+ * training kernel, with a pair of HIP events on the caller's stream.
+ * tuner_profile_read / tuner_profile_read_train wait for the recorded events of
+ * their kind, return the summed kernel time in milliseconds and the number of
+ * launches, and forget them.  Process-wide, not thread-safe; off by default.
  */
 int tuner_profile_enable(int32_t on);
 int tuner_profile_read(double* sweep_ms_total, int64_t* n_sweep_launches);
+int tuner_profile_read_train(double* train_ms_total, int64_t* n_train_launches);
 
 /* Message for the last error on this thread; valid until the next call. */
 const char* tuner_last_error(void);

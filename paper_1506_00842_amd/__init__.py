@@ -28,7 +28,7 @@ EXPORTS = [
     "tuner_space_create", "tuner_space_destroy", "tuner_space_size", "tuner_space_decode",
     "tuner_space_encode", "tuner_space_decode_device_arith", "tuner_workspace_bytes",
     "tuner_predict_topk", "tuner_predict_all", "tuner_decode_range", "tuner_last_error",
-    "tuner_version", "tuner_profile_enable", "tuner_profile_read",
+    "tuner_version", "tuner_profile_enable", "tuner_profile_read", "tuner_profile_read_train",
     "tuner_predict_indices", "tuner_sample_workspace_bytes", "tuner_sample_valid",
     "tuner_train_workspace_bytes", "tuner_train_ensemble", "tuner_mean_relative_error",
     "tuner_best_of",
@@ -124,6 +124,13 @@ def tuner_profile_read():
     """-> (summed sweep-kernel milliseconds, number of launches) since the last read."""
     ms = C.c_double(); n = C.c_int64()
     _check(load_library().tuner_profile_read(C.byref(ms), C.byref(n)))
+    return float(ms.value), int(n.value)
+
+
+def tuner_profile_read_train():
+    """-> (summed training-kernel milliseconds, number of launches) since the last read."""
+    ms = C.c_double(); n = C.c_int64()
+    _check(load_library().tuner_profile_read_train(C.byref(ms), C.byref(n)))
     return float(ms.value), int(n.value)
 
 

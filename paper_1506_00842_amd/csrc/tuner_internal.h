@@ -29,6 +29,11 @@ namespace tuner {
 int set_error(int code, const std::string& msg);
 int hip_error(hipError_t e, const char* what);
 
+// Optional timing of the dominant kernels (HIP events on the caller's stream).
+enum { PROFILE_SWEEP = 0, PROFILE_TRAIN = 1, PROFILE_KINDS = 2 };
+bool profile_on();
+void profile_add(int kind, hipEvent_t begin, hipEvent_t end);
+
 #define TUNER_HIP_TRY(expr)                                   \
   do {                                                        \
     hipError_t e_ = (expr);                                   \

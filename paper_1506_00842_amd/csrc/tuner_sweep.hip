@@ -309,12 +309,13 @@ static Layout make_layout(const Shape& sh, int k) {
   return L;
 }
 
-// Optional timing of the sweep kernel alone (HIP events on the caller's stream).
 struct ProfileState {
   bool on = false;
-  std::vector<std::pair<hipEvent_t, hipEvent_t>> events;
+  std::vector<std::pair<hipEvent_t, hipEvent_t>> events[PROFILE_KINDS];
 };
 static ProfileState g_profile;
+bool profile_on() { return g_profile.on; }
+void profile_add(int kind, hipEvent_t begin, hipEvent_t end) { g_profile.events[kind].emplace_back(begin, end); }
 
 struct DeviceInfo { int n_cu = 0; int max_lds = 0; bool ok = false; };
 
@@ -455,7 +456,7 @@ static int run_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin
     TUNER_HIP_TRY(hipGetLastError());
     if (g_profile.on) {
       TUNER_HIP_TRY(hipEventRecord(ev1, stream));
-      g_profile.events.emplace_back(ev0, ev1);
+      profile_add(PROFILE_SWEEP, ev0, ev1);
     }
   }
 
@@ -536,11 +537,11 @@ int tuner_profile_enable(int32_t on) {
   return TUNER_OK;
 }
 
-int tuner_profile_read(double* sweep_ms_total, int64_t* n_sweep_launches) {
-  if (!sweep_ms_total || !n_sweep_launches) return set_error(TUNER_EINVAL, "null argument");
+static int profile_read(int kind, double* ms_total, int64_t* n_launches) {
+  if (!ms_total || !n_launches) return set_error(TUNER_EINVAL, "null argument");
   double total = 0.0;
   int64_t n = 0;
-  for (auto& ev : tuner::g_profile.events) {
+  for (auto& ev : tuner::g_profile.events[kind]) {
     float ms = 0.0f;
     TUNER_HIP_TRY(hipEventSynchronize(ev.second));
     TUNER_HIP_TRY(hipEventElapsedTime(&ms, ev.first, ev.second));
@@ -549,10 +550,18 @@ int tuner_profile_read(double* sweep_ms_total, int64_t* n_sweep_launches) {
     (void)hipEventDestroy(ev.first);
     (void)hipEventDestroy(ev.second);
   }
-  tuner::g_profile.events.clear();
-  *sweep_ms_total = total;
-  *n_sweep_launches = n;
+  tuner::g_profile.events[kind].clear();
+  *ms_total = total;
+  *n_launches = n;
   return TUNER_OK;
+}
+
+int tuner_profile_read(double* sweep_ms_total, int64_t* n_sweep_launches) {
+  return profile_read(tuner::PROFILE_SWEEP, sweep_ms_total, n_sweep_launches);
+}
+
+int tuner_profile_read_train(double* train_ms_total, int64_t* n_train_launches) {
+  return profile_read(tuner::PROFILE_TRAIN, train_ms_total, n_train_launches);
 }
 
 int tuner_predict_topk(const tuner_space* space, const tuner_model* model, uint64_t index_begin,

@@ -481,8 +481,18 @@ int tuner_train_ensemble(const tuner_space* space, int32_t n_members, int32_t hi
   const size_t lds = (size_t)(1 + var->threads / 128) * nq * 4;
   TUNER_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(var->fn),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+  hipEvent_t ev0 = nullptr, ev1 = nullptr;
+  if (tuner::profile_on()) {
+    TUNER_HIP_TRY(hipEventCreate(&ev0));
+    TUNER_HIP_TRY(hipEventCreate(&ev1));
+    TUNER_HIP_TRY(hipEventRecord(ev0, stream));
+  }
   hipLaunchKernelGGL(var->fn, dim3(n_members), dim3(var->threads), lds, stream, tp);
   TUNER_HIP_TRY(hipGetLastError());
+  if (tuner::profile_on()) {
+    TUNER_HIP_TRY(hipEventRecord(ev1, stream));
+    tuner::profile_add(tuner::PROFILE_TRAIN, ev0, ev1);
+  }
   return TUNER_OK;
 }
 
