@@ -246,6 +246,9 @@ int tuner_sample_valid(const tuner_space* space, uint64_t seed, uint32_t n_sampl
  *   loss_history_dev     DEVICE out, optional, [E][epochs + 1] floats: L_e before each
  *                        update, and last the loss of the final weights
  * A network with no usable training sample keeps its initial weights (loss 0).
+ * All workgroups of the launch (n_members x workgroups_per_network, at most 256)
+ * must be able to run at the same time; on a GPU busy with other work a run may
+ * give up (see barrier_poll_limit), which shows as NaN weights.
  * Limits: 1 <= hidden <= 64, n_samples <= 2^24, epochs >= 0.
  * Workspace: >= tuner_train_workspace_bytes(space, n_samples), 256-byte aligned.
  */
@@ -253,6 +256,15 @@ typedef struct {
   int32_t epochs;
   float learning_rate;
   float momentum;
+  int32_t workgroups_per_network; /* 0: the library's choice; 1..16: each network's samples are
+                                     split over this many workgroups, which add their partial
+                                     gradient sums once per epoch (the result depends on it only
+                                     through the order of fp32 additions) */
+  int32_t barrier_poll_limit;     /* 0: default (2^22).  The workgroups of a network meet at a
+                                     barrier once per epoch; one that has polled this many times
+                                     without seeing the others gives up, the whole run stops, and
+                                     every network that did not finish returns NaN weights and
+                                     NaN losses (never a partial result) */
 } tuner_train_options;
 
 size_t tuner_train_workspace_bytes(const tuner_space* space, uint64_t n_samples);

@@ -42,7 +42,8 @@ class TunerError(RuntimeError):
 
 
 class _TrainOptions(C.Structure):
-    _fields_ = [("epochs", C.c_int32), ("learning_rate", C.c_float), ("momentum", C.c_float)]
+    _fields_ = [("epochs", C.c_int32), ("learning_rate", C.c_float), ("momentum", C.c_float),
+                ("workgroups_per_network", C.c_int32), ("barrier_poll_limit", C.c_int32)]
 
 
 class _Model(C.Structure):
@@ -286,8 +287,10 @@ def tuner_train_workspace_bytes(space, n_samples: int) -> int:
 
 def tuner_train_ensemble(space, n_members, hidden, n_samples, sample_indices_dev, sample_times_dev,
                          sample_parts_dev, initial_weights_dev, epochs, learning_rate, momentum,
-                         weights_out_dev, loss_history_dev, workspace_dev, stream=None):
-    opt = _TrainOptions(int(epochs), float(learning_rate), float(momentum))
+                         weights_out_dev, loss_history_dev, workspace_dev, stream=None,
+                         workgroups_per_network=0, barrier_poll_limit=0):
+    opt = _TrainOptions(int(epochs), float(learning_rate), float(momentum), int(workgroups_per_network),
+                        int(barrier_poll_limit))
     _check(load_library().tuner_train_ensemble(
         space.ptr, int(n_members), int(hidden), int(n_samples), _dp(sample_indices_dev),
         _dp(sample_times_dev), _dp(sample_parts_dev), _dp(initial_weights_dev), C.byref(opt),

@@ -106,7 +106,8 @@ class Tuner:
         return out, found
 
     def train(self, n_members: int, hidden: int, indices, times, parts, initial_weights,
-              epochs: int, learning_rate: float, momentum: float, want_loss: bool = True, stream=None):
+              epochs: int, learning_rate: float, momentum: float, want_loss: bool = True, stream=None,
+              workgroups_per_network: int = 0, barrier_poll_limit: int = 0):
         """-> (weights f32[E * per], loss f32[E, epochs + 1] or None), on the device."""
         idx = _as_index_tensor(indices, self.device)
         n = idx.numel()
@@ -120,7 +121,7 @@ class Tuner:
         w = torch.empty_like(w0)
         loss = torch.zeros((n_members, epochs + 1), dtype=torch.float32, device=self.device) if want_loss else None
         tuner_train_ensemble(self.space, n_members, hidden, n, idx, t, pt, w0, epochs, learning_rate,
-                             momentum, w, loss, ws, stream)
+                             momentum, w, loss, ws, stream, workgroups_per_network, barrier_poll_limit)
         self._keep = (ws, idx, t, pt, w0)
         return w, loss
 

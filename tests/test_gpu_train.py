@@ -129,9 +129,9 @@ def problem(maker, seed, n, E, H, fail_fraction=0.05):
     return sp, idx, t, parts, w0
 
 
-def gpu_train(sp, E, H, idx, t, parts, w0, epochs, eta, mu):
+def gpu_train(sp, E, H, idx, t, parts, w0, epochs, eta, mu, **kw):
     tn = tuner_for(sp)
-    w, loss = tn.train(E, H, idx, t, parts, w0, epochs, eta, mu)
+    w, loss = tn.train(E, H, idx, t, parts, w0, epochs, eta, mu, **kw)
     torch.cuda.synchronize()
     return w.cpu().numpy(), loss.cpu().numpy()
 
@@ -176,6 +176,60 @@ def test_training_matches_oracle(maker, seed, n, E, H, epochs, eta, mu):
     # reproducible bit for bit
     gw2, gl2 = gpu_train(sp, E, H, idx, t, parts, w0, epochs, eta, mu)
     assert np.array_equal(gw, gw2) and np.array_equal(gl, gl2)
+
+
+@pytest.mark.parametrize("split", [1, 2, 3, 7, 16])
+def test_training_any_number_of_workgroups_per_network(split):
+    """The samples of a network are split over several workgroups that exchange partial
+    sums once per epoch: every split must meet the same tolerances (only the order of the
+    fp32 additions differs), ragged slices included (777 samples over 7 workgroups)."""
+    sp, idx, t, parts, w0 = problem(wl.paper_stereo, 51, 777, 5, 30)
+    E, H, epochs, eta, mu = 5, 30, 80, 0.125, 0.75
+    ow, ol = oracle.train_ensemble(sp, E, H, idx, t, parts, w0, epochs, eta, mu)
+    gw, gl = gpu_train(sp, E, H, idx, t, parts, w0, epochs, eta, mu, workgroups_per_network=split)
+    worst_l = np.max(np.abs(gl - ol) / ol)
+    worst_w = np.abs(gw - ow).max() / np.abs(ow).max()
+    say(f"  split {split}: worst loss rel {worst_l:.2e}, weights {worst_w:.2e}")
+    assert worst_l <= 1e-4 and worst_w <= 2e-4
+    gw2, gl2 = gpu_train(sp, E, H, idx, t, parts, w0, epochs, eta, mu, workgroups_per_network=split)
+    assert np.array_equal(gw, gw2) and np.array_equal(gl, gl2)
+
+
+def test_training_long_run_is_reproducible_and_learns():
+    """3000 epochs of the paper-shaped problem, twice: 176 workgroups meet 3001 times per
+    run; any stale read in the exchange of partial sums would show as a difference."""
+    sp, idx, t, parts, w0 = problem(wl.paper_convolution, 61, 2000, 11, 30)
+    a_w, a_l = gpu_train(sp, 11, 30, idx, t, parts, w0, 3000, 0.125, 0.875)
+    b_w, b_l = gpu_train(sp, 11, 30, idx, t, parts, w0, 3000, 0.125, 0.875)
+    assert np.all(np.isfinite(a_w)) and np.all(np.isfinite(a_l))
+    assert np.array_equal(a_w, b_w) and np.array_equal(a_l, b_l)
+    assert np.all(a_l[:, -1] < 0.02 * a_l[:, 0])
+    # the last loss is the loss of the returned weights: check it with the oracle's forward pass
+    _, ol = oracle.train_ensemble(sp, 11, 30, idx, t, parts, a_w, 0, 0.125, 0.875)
+    np.testing.assert_allclose(a_l[:, -1], ol[:, 0], rtol=1e-4)
+
+
+def test_training_gives_up_cleanly_when_the_barrier_times_out():
+    """A poll limit of 1 makes workgroups give up as soon as they have to wait: the kernel
+    must still end, and every network is either complete (bit-identical to a normal run)
+    or all NaN, never a partial result."""
+    sp, idx, t, parts, w0 = problem(wl.paper_convolution, 62, 2000, 11, 30)
+    E, H, epochs = 11, 30, 200
+    per = H * sp.n_params + 2 * H + 1
+    ref_w, ref_l = gpu_train(sp, E, H, idx, t, parts, w0, epochs, 0.125, 0.875)
+    got_w, got_l = gpu_train(sp, E, H, idx, t, parts, w0, epochs, 0.125, 0.875, barrier_poll_limit=1)
+    n_nan = 0
+    for e in range(E):
+        we, le = got_w[e * per:(e + 1) * per], got_l[e]
+        if np.isnan(we).any() or np.isnan(le).any():
+            assert np.isnan(we).all() and np.isnan(le).all()
+            n_nan += 1
+        else:
+            assert np.array_equal(we, ref_w[e * per:(e + 1) * per]) and np.array_equal(le, ref_l[e])
+    say(f"  {n_nan} of {E} networks gave up with a poll limit of 1")
+    # and the library is usable afterwards
+    again_w, again_l = gpu_train(sp, E, H, idx, t, parts, w0, epochs, 0.125, 0.875)
+    assert np.array_equal(again_w, ref_w) and np.array_equal(again_l, ref_l)
 
 
 def test_training_edge_cases():
