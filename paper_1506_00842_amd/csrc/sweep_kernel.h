@@ -73,10 +73,15 @@ __global__ void __launch_bounds__(NW * 64) sweep_kernel(const SweepParams prm) {
     while (lds_pow2 * 2 <= lds_entries) lds_pow2 *= 2;
     if (lds_pow2 < eff_cap && lds_pow2 >= 2u * prm.kp + super_iter) eff_cap = lds_pow2;
   }
+  // The first unit of a workgroup is its own index.  Long ranges take further units
+  // from the queue counter (units differ in cost: invalid ones skip the networks); short
+  // ranges stride through the units instead and touch no atomic at all (a thousand
+  // read-modify-writes of one word would take longer than such a sweep).
+  const bool dynamic = prm.n_units > 8u * gridDim.x;
   uint32_t next0 = 0, next1 = 0;
   if (tid == 0) {
-    next0 = atomicAdd(&prm.hdr->work_counter, 1u);
-    next1 = atomicAdd(&prm.hdr->work_counter, 1u);
+    next0 = blockIdx.x;
+    next1 = dynamic ? gridDim.x + atomicAdd(&prm.hdr->work_counter, 1u) : blockIdx.x + gridDim.x;
   }
 
   for (;;) {
@@ -95,7 +100,7 @@ __global__ void __launch_bounds__(NW * 64) sweep_kernel(const SweepParams prm) {
     if (unit >= prm.n_units) break;
     if (tid == 0) {
       next0 = next1;
-      next1 = atomicAdd(&prm.hdr->work_counter, 1u);
+      next1 = dynamic ? gridDim.x + atomicAdd(&prm.hdr->work_counter, 1u) : next1 + gridDim.x;
     }
 
     if (prm.mode == MODE_TOPK && s_compact) {
