@@ -109,6 +109,8 @@ __global__ void __launch_bounds__(256) prep_kernel(const DevSpace sp, const Prep
 // outputs.  merge_kernel: one pair per workgroup, in place in global memory, for
 // lists too long for LDS.
 // ---------------------------------------------------------------------------
+constexpr uint32_t kWaveMergeMaxKp = 1024;   // lists up to this long are merged one pair per wave
+
 struct MergeParams {
   unsigned long long* pools;
   unsigned long long* extra;   // list index n_pool_lists (the caller's running result)
@@ -139,17 +141,55 @@ __global__ void __launch_bounds__(kMergeThreads) merge_tree_kernel(const MergePa
   auto list_ptr = [&](uint32_t j) -> unsigned long long* {
     return j < mp.n_pool_lists ? mp.pools + (size_t)j * mp.cap : mp.extra;
   };
-  for (uint32_t j = 0; j < slots; ++j) {
-    const uint32_t li = base + j * mp.stride0;
-    if (li < mp.n_lists) {
-      const unsigned long long* src = list_ptr(li);
-      for (uint32_t x = tid; x < kp; x += kMergeThreads) lds[j * kp + x] = src[x];
-    } else {
-      for (uint32_t x = tid; x < kp; x += kMergeThreads) lds[j * kp + x] = kKeyMax;
+  // all lists at once, several loads in flight per thread (a loop over the lists would pay
+  // one memory latency per list)
+  const uint32_t total = slots * kp;
+  for (uint32_t t0 = 0; t0 < total; t0 += 4 * kMergeThreads) {
+    unsigned long long v[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const uint32_t t = t0 + q * kMergeThreads + tid;
+      const uint32_t j = t / kp, x = t - j * kp;
+      const uint32_t li = base + j * mp.stride0;
+      v[q] = (t < total && li < mp.n_lists) ? list_ptr(li)[x] : kKeyMax;
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const uint32_t t = t0 + q * kMergeThreads + tid;
+      if (t < total) lds[t] = v[q];
     }
   }
   __syncthreads();
   const uint32_t half = kp >> 1;
+  if (kp <= kWaveMergeMaxKp) {
+    // Short lists: one wave per pair of lists.  A wave's LDS instructions execute in
+    // program order, so the steps of its merge network need no workgroup barrier, only a
+    // compiler fence; the workgroup meets once per tree level.
+    const uint32_t wave = tid >> 6, lane = tid & 63;
+    for (uint32_t s = 1; s < slots; s <<= 1) {
+      const uint32_t npairs = slots / (2 * s);
+      for (uint32_t m = wave; m < npairs; m += kMergeThreads / 64) {
+        unsigned long long* A = lds + (size_t)(2 * m * s) * kp;
+        const unsigned long long* B = A + (size_t)s * kp;
+        for (uint32_t i = lane; i < kp; i += 64) {
+          const unsigned long long a = A[i], b = B[kp - 1 - i];
+          A[i] = a < b ? a : b;
+        }
+        for (uint32_t j = half; j > 0; j >>= 1) {
+          __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+          __builtin_amdgcn_wave_barrier();
+          __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+          for (uint32_t u = lane; u < half; u += 64) {
+            const uint32_t i = ((u & ~(j - 1)) << 1) | (u & (j - 1));
+            const uint32_t l = i | j;
+            const unsigned long long x = A[i], y = A[l];
+            if (x > y) { A[i] = y; A[l] = x; }
+          }
+        }
+      }
+      __syncthreads();
+    }
+  } else {
   for (uint32_t s = 1; s < slots; s <<= 1) {
     const uint32_t npairs = slots / (2 * s);
     // A[i] = min(A[i], B[kp-1-i]) over every pair (A = slot 2 m s, B = slot 2 m s + s)
@@ -171,6 +211,7 @@ __global__ void __launch_bounds__(kMergeThreads) merge_tree_kernel(const MergePa
       }
       __syncthreads();
     }
+  }
   }
   unsigned long long* dst = list_ptr(base);
   for (uint32_t x = tid; x < kp; x += kMergeThreads) dst[x] = lds[x];
@@ -467,9 +508,9 @@ static int run_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin
     const size_t merge_lds_max = std::min<size_t>((size_t)di.max_lds, 128u << 10);
     bool finalized = false;
     if (2 * list_bytes <= merge_lds_max) {
-      // in LDS, up to 16 lists per workgroup and launch
+      // in LDS, up to 32 lists per workgroup and launch
       uint32_t max_levels = 0;
-      while (max_levels < 4 && (list_bytes << (max_levels + 1)) <= merge_lds_max) ++max_levels;
+      while (max_levels < 5 && (list_bytes << (max_levels + 1)) <= merge_lds_max) ++max_levels;
       TUNER_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(merge_tree_kernel),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)merge_lds_max));
       uint32_t live = n_lists, stride = 1;
