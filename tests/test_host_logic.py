@@ -187,6 +187,71 @@ def test_predict_argument_errors_before_any_gpu_work():
     assert L.tuner_decode_range(None, 0, 1, None, None, None, None) == T.TUNER_EINVAL
 
 
+def test_tuner_stage_argument_errors_before_any_gpu_work():
+    """Sampler, training, list evaluation, metric and second-stage entry points reject bad
+    calls on the host (no HIP call is reached)."""
+    L = T.load_library()
+    w = wl.conv_shaped()
+    h = make_space(w.space)
+    fake = C.c_void_p(0x4000)
+    # sampler
+    assert T.tuner_sample_workspace_bytes(1000) % 256 == 0
+    assert T.tuner_sample_workspace_bytes(1 << 24) >= 8 * (1 << 25)
+    with pytest.raises(T.TunerError):
+        T.tuner_sample_workspace_bytes(0)
+    with pytest.raises(T.TunerError):
+        T.tuner_sample_workspace_bytes((1 << 24) + 1)
+    big = 1 << 40
+    assert L.tuner_sample_valid(None, 1, 10, 100, fake, fake, fake, big, None) == T.TUNER_EINVAL
+    assert L.tuner_sample_valid(h.ptr, 1, 10, 100, None, fake, fake, big, None) == T.TUNER_EINVAL
+    assert L.tuner_sample_valid(h.ptr, 1, 0, 100, fake, fake, fake, big, None) == T.TUNER_EINVAL
+    assert L.tuner_sample_valid(h.ptr, 1, 10, 9, fake, fake, fake, big, None) == T.TUNER_EINVAL
+    assert L.tuner_sample_valid(h.ptr, 1, 10, (1 << 24) + 1, fake, fake, fake, big, None) == T.TUNER_ETOOLARGE
+    assert L.tuner_sample_valid(h.ptr, 1, 10, 100, fake, fake, None, big, None) == T.TUNER_EWORKSPACE
+    assert L.tuner_sample_valid(h.ptr, 1, 10, 100, fake, fake, fake, 64, None) == T.TUNER_EWORKSPACE
+    assert L.tuner_sample_valid(h.ptr, 1, 10, 100, fake, fake, C.c_void_p(0x4010), big, None) == T.TUNER_EWORKSPACE
+    # training
+    need = T.tuner_train_workspace_bytes(h, 2000)
+    assert need % 256 == 0 and need > 2000 * 4 * 16
+    with pytest.raises(T.TunerError):
+        T.tuner_train_workspace_bytes(h, (1 << 24) + 1)
+
+    def train(space=h.ptr, E=11, H=30, n=2000, idx=fake, t=fake, parts=fake, w0=fake, opt=(10, 0.1, 0.5, 0, 0),
+              out=fake, ws=fake, ws_bytes=need):
+        o = T._TrainOptions(*opt) if opt is not None else None
+        return L.tuner_train_ensemble(space, E, H, n, idx, t, parts, w0, C.byref(o) if o is not None else None,
+                                      out, None, ws, ws_bytes, None)
+    assert train(space=None) == T.TUNER_EINVAL
+    assert train(w0=None) == T.TUNER_EINVAL
+    assert train(out=None) == T.TUNER_EINVAL
+    assert train(opt=None) == T.TUNER_EINVAL
+    assert train(idx=None) == T.TUNER_EINVAL
+    assert train(E=0) == T.TUNER_EINVAL
+    assert train(H=0) == T.TUNER_EINVAL
+    assert train(H=65) == T.TUNER_ETOOLARGE
+    assert train(n=(1 << 24) + 1) == T.TUNER_ETOOLARGE
+    assert train(opt=(-1, 0.1, 0.5, 0, 0)) == T.TUNER_EINVAL
+    assert train(opt=(10, float("nan"), 0.5, 0, 0)) == T.TUNER_EINVAL
+    assert train(opt=(10, 0.1, 0.5, 17, 0)) == T.TUNER_EINVAL
+    assert train(opt=(10, 0.1, 0.5, 0, -1)) == T.TUNER_EINVAL
+    assert train(ws=None) == T.TUNER_EWORKSPACE
+    assert train(ws_bytes=need - 1) == T.TUNER_EWORKSPACE
+    assert train(ws=C.c_void_p(0x4010)) == T.TUNER_EWORKSPACE
+    assert "workspace" in T.tuner_last_error()
+    # evaluation at a list, metric, second stage
+    m = T.ModelHandle(8, w.model.widths, _FakeWeights())
+    assert L.tuner_predict_indices(h.ptr, C.byref(m.c), 10, None, fake, None, fake, 1 << 30, None) == T.TUNER_EINVAL
+    assert L.tuner_predict_indices(h.ptr, C.byref(m.c), 10, fake, None, None, fake, 1 << 30, None) == T.TUNER_EINVAL
+    assert L.tuner_predict_indices(h.ptr, C.byref(m.c), 0, None, fake, None, None, 0, None) == T.TUNER_OK   # nothing to do
+    assert L.tuner_predict_indices(h.ptr, C.byref(m.c), 10, fake, fake, None, fake, 16, None) == T.TUNER_EWORKSPACE
+    assert L.tuner_mean_relative_error(10, None, fake, fake, fake, None) == T.TUNER_EINVAL
+    assert L.tuner_mean_relative_error(10, fake, fake, None, fake, None) == T.TUNER_EINVAL
+    assert L.tuner_mean_relative_error((1 << 31) + 1, fake, fake, fake, fake, None) == T.TUNER_ETOOLARGE
+    assert L.tuner_best_of(10, None, fake, fake, None) == T.TUNER_EINVAL
+    assert L.tuner_best_of(10, fake, None, fake, None) == T.TUNER_EINVAL
+    assert L.tuner_best_of((1 << 31) + 1, fake, fake, fake, None) == T.TUNER_ETOOLARGE
+
+
 def test_binding_fails_loudly_without_the_library(monkeypatch):
     monkeypatch.setattr(T, "_lib", None)
     monkeypatch.setattr(T, "LIB_PATH", "/nonexistent/libtuner_hip.so")
