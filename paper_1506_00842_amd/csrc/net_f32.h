@@ -13,7 +13,8 @@
 // traffic.  -log2(e) is folded into the hidden layers' weights and biases.
 //
 // Packed member (fp32 words):
-//   W1A [NT1][KS1/4][64 lanes][4]   lane (n, h), steps s = 4*sg + j:
+//   W1A [NT1][ceil(KS1/4)][64 lanes][4]   lane (n, h), steps s = 4*sg + j (KS1 is even;
+//        the last group of an odd number of step pairs uses j = 0, 1 only):
 //        unit = 32 t + n, input f = 2 s + h: W1[unit][f], b1[unit] at f = P, else 0
 //   W2A [NT2][NT1][4][64 lanes][4]  lane (n, h): W2[32 u + n][32 t + 8 g + 4 h + j]
 //   b2A [NT2][4][2][4]              b2[32 u + 8 g + 4 h + j]
@@ -68,15 +69,24 @@ struct F32Net {
 #pragma unroll
       for (int v = 0; v < 16; ++v) a1[t][v] = 0.0f;
     const float4* w1 = reinterpret_cast<const float4*>(w + o.w1);
+    constexpr int KG = (KS1 + 3) / 4;       // groups of 4 steps in the packed layout
 #pragma unroll
     for (int sg = 0; sg < KS1 / 4; ++sg) {
 #pragma unroll
       for (int t = 0; t < NT1; ++t) {
-        const float4 a = w1[(t * (KS1 / 4) + sg) * 64 + lane];
+        const float4 a = w1[(t * KG + sg) * 64 + lane];
         a1[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, f.x[4 * sg + 0], a1[t], 0, 0, 0);
         a1[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, f.x[4 * sg + 1], a1[t], 0, 0, 0);
         a1[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, f.x[4 * sg + 2], a1[t], 0, 0, 0);
         a1[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, f.x[4 * sg + 3], a1[t], 0, 0, 0);
+      }
+    }
+    if constexpr (KS1 % 4 == 2) {
+#pragma unroll
+      for (int t = 0; t < NT1; ++t) {
+        const float2 a = *reinterpret_cast<const float2*>(&w1[(t * KG + KS1 / 4) * 64 + lane]);
+        a1[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, f.x[KS1 - 2], a1[t], 0, 0, 0);
+        a1[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, f.x[KS1 - 1], a1[t], 0, 0, 0);
       }
     }
     // sigmoid in three passes (exp2, +1, rcp) so that no instruction waits on the
@@ -152,11 +162,12 @@ __device__ inline float pack_word_f32(const Shape& sh, const float* raw, int q) 
   const int HL = sh.H2 ? sh.H2 : sh.H1;
   float v = 0.0f;
   if (q < sh.o_w2) {                                    // W1A
+    const int KG = (sh.KS + 3) / 4;
     const int j = q & 3, lane = (q >> 2) & 63, rest = q >> 8;
-    const int sg = rest % (sh.KS / 4), t = rest / (sh.KS / 4);
+    const int sg = rest % KG, t = rest / KG;
     const int n = lane & 31, h = lane >> 5, s = 4 * sg + j;
     const int unit = 32 * t + n, f = 2 * s + h;
-    if (unit < sh.H1) {
+    if (unit < sh.H1 && s < sh.KS) {
       if (f < sh.P) v = raw[r_w1 + unit * sh.P + f] * kNegLog2e;
       else if (f == sh.P) v = raw[r_b1 + unit] * kNegLog2e;
     }

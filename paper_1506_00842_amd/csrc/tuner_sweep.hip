@@ -290,9 +290,9 @@ static int make_shape(const tuner_space* sp, const tuner_model* m, Shape* sh) {
   sh->raw_member_floats = sh->P * sh->H1 + sh->H1 + (sh->H2 ? sh->H1 * sh->H2 + sh->H2 + sh->H2 : sh->H1) + 1;
   if (sh->net == NET_F32_MFMA) {
     sh->NPL = 1;
-    sh->KS = round_up(sh->P + 1, 8) / 2;       // steps of 2 inputs (bias column included), multiple of 4
+    sh->KS = round_up(sh->P + 1, 4) / 2;       // steps of 2 inputs (bias column included), even
     sh->o_w1 = 0;
-    sh->o_w2 = sh->NT1 * sh->KS * 64;
+    sh->o_w2 = sh->NT1 * round_up(sh->KS, 4) * 64;   // stored in groups of 4 steps
     sh->o_b1 = sh->o_w2 + sh->NT2 * sh->NT1 * 16 * 64;   // (no separate b1 table: bias rides in W1A)
     sh->o_b2 = sh->o_b1;
     sh->o_wo = sh->o_b2 + sh->NT2 * 32;
