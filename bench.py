@@ -167,6 +167,9 @@ def main():
     ap.add_argument("--net", default="f32-mfma", choices=["f32-mfma", "split16", "bf16", "valu"],
                     help="f32-mfma: fp32 matrix instructions; split16: two-plane f16 split, fp32 "
                          "accumulate (fp32 tolerance); bf16: bf16 operands (1e-2 tolerance)")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step in a HIP graph and time its replays (the sweep kernel's own "
+                         "duration then comes from an eager pass after the timed region)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-other-nets", action="store_true",
                     help="skip the short untimed-region comparison runs of the other network evaluations")
@@ -221,13 +224,37 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    T.tuner_profile_enable(True)
-    T.tuner_profile_read()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
+    if args.graph:
+        side = torch.cuda.Stream()
+        eager_stream, stream = stream, side
+        side.wait_stream(eager_stream)
+        with torch.cuda.stream(side):
+            step()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+        stream = eager_stream
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        T.tuner_profile_enable(True)
+        T.tuner_profile_read()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+    else:
+        T.tuner_profile_enable(True)
+        T.tuner_profile_read()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
     sweep_ms, n_launch = T.tuner_profile_read()
     T.tuner_profile_enable(False)
 
@@ -257,7 +284,7 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "n_configs": N, "n_valid": n_valid, "k": w.k,
                    "members": m.n_members, "widths": list(m.widths), "mode": args.mode,
-                   "chunk": chunk, "net": args.net},
+                   "chunk": chunk, "net": args.net, "hip_graph": bool(args.graph)},
         "roofline": roof,
     }
     if not args.no_other_nets and args.mode == "topk":

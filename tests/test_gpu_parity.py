@@ -332,3 +332,49 @@ def test_adversarial_order_descending_predictions():
     torch.cuda.synchronize()
     gv, gi = sw.topk_host()
     parity.check_topk(gv, gi, oy, ov, 0, 1000)
+
+
+def test_topk_and_predict_all_replay_from_a_hip_graph():
+    """The library only enqueues kernels (no allocation, copy, memset or synchronisation),
+    so a caller may capture its calls in a HIP graph.  A captured chunked top-k sweep and
+    a captured predict_all are replayed several times with eager work and synchronisations
+    between the replays; every replay must reproduce the eager result bit for bit."""
+    w = wl.paper_raycasting()
+    n = w.space.n_configs
+    half = n // 2 + 12345                      # two ragged chunks merged on the device
+    sw = sweep_for(w)
+    sw.topk(0, half)
+    sw.topk(half, n - half, merge=True)
+    pred_eager, _ = sw.predict_all(0, n, want_mask=False)
+    torch.cuda.synchronize()
+    ref_v, ref_i = sw.topk_host()
+    ref_pred = pred_eager.clone()
+    oy, ov, _ = oracle.predict_range(w.space, w.model, 0, n, threads=THREADS)
+    parity.check_topk(ref_v, ref_i, oy, ov, 0, w.k)
+
+    pred = torch.empty(n, dtype=torch.float32, device=sw.device)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):              # warm-up on the capture stream
+        sw.topk(0, half)
+        sw.predict_all(0, n, want_mask=False, out=pred)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        sw.topk(0, half)
+        sw.topk(half, n - half, merge=True)
+        sw.predict_all(0, n, want_mask=False, out=pred)
+    for rep in range(4):
+        # eager work between replays: scribble over the outputs and run another sweep
+        sw.values.fill_(-1.0)
+        sw.indices.fill_(7)
+        sw.n_found.fill_(0)
+        pred.fill_(float("nan"))
+        sw.topk(rep * 1000, 50000)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        gv, gi = sw.topk_host()
+        assert np.array_equal(gv, ref_v) and np.array_equal(gi, ref_i), f"replay {rep}"
+        assert torch.equal(pred, ref_pred), f"replay {rep}"
