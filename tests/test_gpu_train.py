@@ -146,6 +146,8 @@ TRAIN_CASES = [  # maker, seed, n, E, H, epochs, eta, mu
     (wl.streamed, 25, 1500, 8, 64, 40, 0.0625, 0.75),                     # 20 inputs, 64 units
     (lambda: wl.many_params(25, [8], 1, 3), 26, 300, 2, 17, 40, 0.0625, 0.5),
     (wl.large, 27, 4000, 2, 30, 200, 0.125, 0.875),
+    (lambda: wl.many_params(31, [8], 1, 3), 28, 400, 3, 64, 30, 0.0625, 0.5),   # widest kernel: 31 inputs, 64 units
+    (lambda: wl.many_params(31, [8], 1, 3), 29, 900, 2, 20, 30, 0.0625, 0.5),
 ]
 
 
