@@ -17,6 +17,8 @@ constexpr int kSpaceBytes = (sizeof(DevSpace) + 255) / 256 * 256;
 constexpr float kNegLog2e = -1.44269504088896340736f;
 
 enum { MODE_TOPK = 0, MODE_ALL = 1 };
+// validity of the configurations of one chunk, known before the sweep
+enum { CHUNK_ALL_INVALID = 0, CHUNK_ALL_VALID = 1, CHUNK_MIXED = 2 };
 // how the network is evaluated
 enum { NET_F32_MFMA = 0, NET_BF16 = 1, NET_F16X2 = 2, NET_F32_VALU = 3 };
 
@@ -26,7 +28,8 @@ struct WsHeader {
   unsigned long long tau;     // upper bound (as a key) of the final k-th smallest key
   uint32_t work_counter;      // next chunk of the dynamic queue
   float bo_sum;               // sum of the members' output biases
-  uint32_t pad[12];
+  uint32_t n_live;            // entries of the live-chunk list (long constrained ranges)
+  uint32_t pad[11];
 };
 
 // Model shape and the layout of one packed member, in 32-bit words.
@@ -53,6 +56,9 @@ struct SweepParams {
   float inv_members;          // 1 / n_members, rounded once from double
   uint32_t cap, kp;           // pool capacity per workgroup, k rounded up to a power of two
   uint32_t lds_entries;       // keys that fit the LDS region after the space tables (weights / sort scratch)
+  int32_t dynamic;            // units beyond a workgroup's first come from the queue counter (else strided)
+  const uint32_t* live;       // optional list of chunks to sweep: chunk index | state << 30; its length is
+                              // hdr->n_live (chunks with no valid configuration are left out of top-k sweeps)
   NetOffsets off;
   const DevSpace* space;      // in the workspace
   const uint32_t* packed;

@@ -74,10 +74,15 @@ __global__ void __launch_bounds__(NW * 64) sweep_kernel(const SweepParams prm) {
     if (lds_pow2 < eff_cap && lds_pow2 >= 2u * prm.kp + super_iter) eff_cap = lds_pow2;
   }
   // The first unit of a workgroup is its own index.  Long ranges take further units
-  // from the queue counter (units differ in cost: invalid ones skip the networks); short
-  // ranges stride through the units instead and touch no atomic at all (a thousand
-  // read-modify-writes of one word would take longer than such a sweep).
-  const bool dynamic = prm.n_units > 8u * gridDim.x;
+  // from the queue counter (units differ in cost); short ranges stride through the units
+  // instead and touch no atomic at all (a thousand read-modify-writes of one word would
+  // take longer than such a sweep).  Long constrained ranges come with a list of the
+  // chunks to sweep, made by classify_kernel: runs of chunks without any valid
+  // configuration would otherwise turn the queue counter into the bottleneck (every
+  // workgroup claims such units as fast as the atomic unit serves them).
+  const bool dynamic = prm.dynamic != 0;
+  const uint32_t n_chunks = prm.live ? prm.hdr->n_live : prm.n_chunks;
+  const uint32_t n_units = prm.live ? (n_chunks + (uint32_t)prm.super - 1u) / (uint32_t)prm.super : prm.n_units;
   uint32_t next0 = 0, next1 = 0;
   if (tid == 0) {
     next0 = blockIdx.x;
@@ -97,7 +102,7 @@ __global__ void __launch_bounds__(NW * 64) sweep_kernel(const SweepParams prm) {
     }
     __syncthreads();
     const uint32_t unit = __builtin_amdgcn_readfirstlane(s_chunk);
-    if (unit >= prm.n_units) break;
+    if (unit >= n_units) break;
     if (tid == 0) {
       next0 = next1;
       next1 = dynamic ? gridDim.x + atomicAdd(&prm.hdr->work_counter, 1u) : next1 + gridDim.x;
@@ -125,8 +130,11 @@ __global__ void __launch_bounds__(NW * 64) sweep_kernel(const SweepParams prm) {
     const unsigned long long tau = s_tau;
 
     for (uint32_t sub = 0; sub < (uint32_t)prm.super; ++sub) {
-    const uint32_t chunk = unit * (uint32_t)prm.super + sub;
-    if (chunk >= prm.n_chunks) break;
+    const uint32_t slot = unit * (uint32_t)prm.super + sub;
+    if (slot >= n_chunks) break;
+    const uint32_t entry = prm.live ? prm.live[slot] : (slot | ((uint32_t)CHUNK_MIXED << 30));
+    const uint32_t chunk = entry & 0x3fffffffu;
+    const uint32_t state = __builtin_amdgcn_readfirstlane(entry >> 30);
 
     // ---- validity, then digits -> features, for this wave's R tiles
     typename Net::Feat feat[R];
@@ -143,14 +151,18 @@ __global__ void __launch_bounds__(NW * 64) sweep_kernel(const SweepParams prm) {
       if (prm.index_list) i = (uint32_t)c < left ? prm.index_list[t0 + (uint32_t)c] : 0u;
       idx[r] = i;
       bool v = (uint32_t)c < left;
-      for (int cc = 0; cc < n_constraints; ++cc) {
-        int ps;
-        if constexpr (kTile == 32) {
-          ps = pair_sum(rule_partial_sum(sp, cc, i, h, 2, pow2));   // the lane pair splits the entries
-        } else {
-          ps = rule_partial_sum(sp, cc, i, 0, 1, pow2);
+      if (state == CHUNK_MIXED) {
+        for (int cc = 0; cc < n_constraints; ++cc) {
+          int ps;
+          if constexpr (kTile == 32) {
+            ps = pair_sum(rule_partial_sum(sp, cc, i, h, 2, pow2));   // the lane pair splits the entries
+          } else {
+            ps = rule_partial_sum(sp, cc, i, 0, 1, pow2);
+          }
+          v = v && (ps <= sp.bound[cc]);
         }
-        v = v && (ps <= sp.bound[cc]);
+      } else {
+        v = v && state == CHUNK_ALL_VALID;
       }
       ok[r] = v;
       any[r] = __ballot(v) != 0ull;

@@ -94,6 +94,7 @@ __global__ void __launch_bounds__(256) prep_kernel(const DevSpace sp, const Prep
     for (int e = 0; e < sh.E; ++e) bo += pp.raw[(size_t)e * sh.raw_member_floats + r_bo];
     pp.hdr->bo_sum = bo;
     pp.hdr->work_counter = 0u;
+    pp.hdr->n_live = 0u;
     pp.hdr->tau = (pp.merge && found == pp.k && pp.k > 0)
                       ? make_key(pp.in_values[pp.k - 1], pp.in_indices[pp.k - 1]) : kKeyMax;
   }
@@ -327,15 +328,61 @@ static const Variant* find_variant(const Shape& sh) {
   return nullptr;
 }
 
+// ---------------------------------------------------------------------------
+// classify: for a long constrained range, the list of chunks the sweep has to visit.
+// A chunk whose rule parameters keep their digits over all its configurations (the
+// quotient index / stride is the same at both ends, hence throughout) is valid or
+// invalid as a whole.  Chunks without any valid configuration are left out of top-k
+// sweeps; the others carry their state, so that wholly valid chunks skip the per-lane
+// rule sums.  The order of the list does not matter to any result.
+// ---------------------------------------------------------------------------
+struct ClassifyParams {
+  uint64_t begin, count;
+  uint32_t n_chunks, iter;
+  int32_t keep_invalid;       // predict_all writes +inf for them
+  uint32_t* live;
+  WsHeader* hdr;
+};
+
+__global__ void __launch_bounds__(256) classify_kernel(const DevSpace sp, const ClassifyParams cp) {
+  const bool pow2 = sp.all_pow2 != 0;
+  const uint32_t lane = threadIdx.x & 63;
+  for (uint32_t base = blockIdx.x * blockDim.x; base < cp.n_chunks; base += gridDim.x * blockDim.x) {
+    const uint32_t c = base + threadIdx.x;
+    const bool in = c < cp.n_chunks;
+    uint32_t state = CHUNK_ALL_INVALID;
+    if (in) {
+      const uint64_t t0 = (uint64_t)c * cp.iter;
+      const uint64_t left = cp.count - t0 < (uint64_t)cp.iter ? cp.count - t0 : (uint64_t)cp.iter;
+      const uint32_t lo = (uint32_t)(cp.begin + t0), hi = (uint32_t)(cp.begin + t0 + left - 1);
+      bool uniform = true;
+      for (int cc = 0; cc < sp.n_constraints; ++cc)
+        for (int e = sp.entry_begin[cc]; e < sp.entry_begin[cc + 1]; ++e) {
+          const int p = (int)sp.entry[e].param;
+          const uint32_t qa = pow2 ? lo >> sp.pa[p].shift : fast_div(lo, sp.pa[p].stride_mul, sp.pb[p].stride_sh);
+          const uint32_t qb = pow2 ? hi >> sp.pa[p].shift : fast_div(hi, sp.pa[p].stride_mul, sp.pb[p].stride_sh);
+          uniform = uniform && qa == qb;
+        }
+      state = uniform ? (is_valid(sp, lo, pow2) ? CHUNK_ALL_VALID : CHUNK_ALL_INVALID) : CHUNK_MIXED;
+    }
+    const bool keep = in && (state != CHUNK_ALL_INVALID || cp.keep_invalid);
+    const unsigned long long bal = __ballot(keep);
+    uint32_t pos = 0;
+    if (lane == 0 && bal) pos = atomicAdd(&cp.hdr->n_live, (uint32_t)__popcll(bal));
+    pos = __shfl(pos, 0);
+    if (keep) cp.live[pos + __popcll(bal & ((1ull << lane) - 1ull))] = c | (state << 30);
+  }
+}
+
 struct Layout {
-  size_t o_hdr, o_space, o_packed, o_pools, o_extra, total;
+  size_t o_hdr, o_space, o_packed, o_pools, o_extra, o_live, total;
   uint32_t cap, kp;
 };
 
 static uint32_t host_next_pow2(uint32_t v) { uint32_t p = 1; while (p < v) p <<= 1; return p; }
 
 
-static Layout make_layout(const Shape& sh, int k) {
+static Layout make_layout(const Shape& sh, int k, uint64_t n_configs, const Variant* var) {
   Layout L{};
   auto al = [](size_t v) { return (v + 255) / 256 * 256; };
   L.o_hdr = 0;
@@ -346,7 +393,10 @@ static Layout make_layout(const Shape& sh, int k) {
   const uint32_t unit_max = (uint32_t)(kMaxIter * kMaxSuper);
   L.cap = k > 0 ? 4u * (L.kp > unit_max ? L.kp : unit_max) : 0;
   L.o_extra = L.o_pools + (size_t)kMaxGroups * L.cap * 8;
-  L.total = L.o_extra + al((size_t)L.kp * 8);
+  L.o_live = L.o_extra + al((size_t)L.kp * 8);
+  // live-chunk list: long ranges only, whose chunks have the variant's full size
+  const uint64_t full = (uint64_t)var->waves * var->R * var->tile;
+  L.total = L.o_live + al((size_t)((n_configs + full - 1) / full) * 4);
   return L;
 }
 
@@ -388,7 +438,7 @@ static int run_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin
   } else if (begin > sp->n_configs || count > sp->n_configs - begin) {
     return set_error(TUNER_EINVAL, "range outside the space");
   }
-  const Layout L = make_layout(sh, k);
+  const Layout L = make_layout(sh, k, sp->n_configs, var);
   if (!ws || ws_bytes < L.total) return set_error(TUNER_EWORKSPACE, "workspace missing or too small");
   if ((reinterpret_cast<uintptr_t>(ws) & 255) != 0) return set_error(TUNER_EWORKSPACE, "workspace not 256-byte aligned");
   DeviceInfo di;
@@ -475,6 +525,25 @@ static int run_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin
     sw.pools = pools;
     sw.pred = pred;
     sw.mask = mask;
+    // long ranges take units from the queue counter; constrained ones first get the list
+    // of chunks worth visiting
+    sw.dynamic = n_units > 8u * groups ? 1 : 0;
+    sw.live = nullptr;
+    if (sw.dynamic && !index_list && sp->n_constraints > 0 && r_used == var->R) {   // the list is sized for full chunks
+      uint32_t* live = reinterpret_cast<uint32_t*>(base + L.o_live);
+      ClassifyParams cp{};
+      cp.begin = begin;
+      cp.count = count;
+      cp.n_chunks = n_chunks;
+      cp.iter = (uint32_t)iter;
+      cp.keep_invalid = mode == MODE_ALL ? 1 : 0;
+      cp.live = live;
+      cp.hdr = hdr;
+      hipLaunchKernelGGL(classify_kernel, dim3(std::min<uint32_t>(1024u, (n_chunks + 255u) / 256u)), dim3(256), 0,
+                         stream, sp->dev, cp);
+      TUNER_HIP_TRY(hipGetLastError());
+      sw.live = live;
+    }
     // the region after the space tables holds a stage of weights and doubles as sort
     // scratch for the candidate pool: make it large enough for a pool that is compacted
     // when it reaches 2 k + one queue unit, if the LDS allows
@@ -570,7 +639,7 @@ size_t tuner_workspace_bytes(const tuner_space* space, const tuner_model* model,
   tuner::Shape sh{};
   if (tuner::make_shape(space, model, &sh)) return 0;
   if (!tuner::find_variant(sh)) { set_error(TUNER_ETOOLARGE, "no kernel variant for this model shape"); return 0; }
-  return tuner::make_layout(sh, k).total;
+  return tuner::make_layout(sh, k, space->n_configs, tuner::find_variant(sh)).total;
 }
 
 int tuner_profile_enable(int32_t on) {

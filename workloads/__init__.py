@@ -407,10 +407,18 @@ def large_with_members(n_members: int) -> Workload:
                     n_valid=63_700_992)
 
 
+def large_unconstrained() -> Workload:
+    """The 2**27 space without validity rules (the paper's own sweep masks nothing)."""
+    w = large()
+    sp = w.space
+    free = Space("large-2^27-unconstrained", sp.values, sp.scales)
+    return Workload("cfg3-unconstrained", free, w.model, w.k, n_valid=free.n_configs)
+
+
 BENCH_WORKLOADS = {
     "cfg3-E1": lambda: large_with_members(1), "cfg3-E8": lambda: large_with_members(8),
     "cfg1": tiny, "cfg2": conv_shaped, "cfg3": large, "cfg4": wide, "cfg5": streamed,
-    "cfg3-2^26": large_as_written,
+    "cfg3-2^26": large_as_written, "cfg3-unconstrained": lambda: large_unconstrained(),
     "paper-convolution": paper_convolution, "paper-raycasting": paper_raycasting,
     "paper-stereo": paper_stereo,
 }
