@@ -56,6 +56,24 @@ __global__ void __launch_bounds__(NW * 64) sweep_kernel(const SweepParams prm) {
     const int n4 = nm * prm.member_words / 4;
     for (int x = tid; x < n4; x += kThreads) dst[x] = src[x];
   };
+  // The same copy without registers and without waiting: LDS-direct loads (every wave
+  // moves 64 x 16 bytes per instruction; lane l's bytes land at the wave's base + 16 l).
+  // Completion is the wave's vmcnt; the stage is visible to the workgroup after
+  // s_waitcnt vmcnt(0) and a barrier.
+  auto issue_stage = [&](int st, int buf) {
+    const int first = st * prm.members_per_stage;
+    int nm = prm.n_members - first;
+    nm = nm < prm.members_per_stage ? nm : prm.members_per_stage;
+    const uint4* src = reinterpret_cast<const uint4*>(prm.packed + (size_t)first * prm.member_words);
+    uint4* dst = reinterpret_cast<uint4*>(wts + (size_t)buf * prm.stage_words);
+    const int n4 = nm * prm.member_words / 4;
+    for (int x = wave_u * 64; x < n4; x += kThreads) {
+      if (x + lane < n4)
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + x + lane),
+                                         (__attribute__((address_space(3))) void*)(dst + x), 16, 0, 0);
+    }
+  };
+  const bool double_buffer = prm.double_buffer != 0;
   if (prm.n_stages == 1) load_stage(0);
   const float bo_sum = prm.hdr->bo_sum;
   const bool pow2 = prm.space->all_pow2 != 0;
@@ -129,9 +147,13 @@ __global__ void __launch_bounds__(NW * 64) sweep_kernel(const SweepParams prm) {
     }
     const unsigned long long tau = s_tau;
 
-    for (uint32_t sub = 0; sub < (uint32_t)prm.super; ++sub) {
+    // chunks of this unit; with two stage buffers the first stage's weights start
+    // their way into LDS now and every later stage while its predecessor is evaluated
+    const uint32_t n_sub = min((uint32_t)prm.super, n_chunks - unit * (uint32_t)prm.super);
+    uint32_t stage_seq = 0;
+    if (double_buffer) issue_stage(0, 0);
+    for (uint32_t sub = 0; sub < n_sub; ++sub) {
     const uint32_t slot = unit * (uint32_t)prm.super + sub;
-    if (slot >= n_chunks) break;
     const uint32_t entry = prm.live ? prm.live[slot] : (slot | ((uint32_t)CHUNK_MIXED << 30));
     const uint32_t chunk = entry & 0x3fffffffu;
     const uint32_t state = __builtin_amdgcn_readfirstlane(entry >> 30);
@@ -173,7 +195,17 @@ __global__ void __launch_bounds__(NW * 64) sweep_kernel(const SweepParams prm) {
 
     // ---- ensemble
     for (int st = 0; st < prm.n_stages; ++st) {
-      if (prm.n_stages > 1) {
+      const uint32_t* stage = wts;
+      if (double_buffer) {
+        // stage st has landed in its buffer, and every wave has left the other buffer
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+        __syncthreads();
+        const int buf = (int)(stage_seq & 1u);
+        ++stage_seq;
+        if (st + 1 < prm.n_stages) issue_stage(st + 1, buf ^ 1);
+        else if (sub + 1 < n_sub) issue_stage(0, buf ^ 1);
+        stage = wts + (size_t)buf * prm.stage_words;
+      } else if (prm.n_stages > 1) {
         __syncthreads();
         load_stage(st);
         __syncthreads();
@@ -182,7 +214,7 @@ __global__ void __launch_bounds__(NW * 64) sweep_kernel(const SweepParams prm) {
       int nm = prm.n_members - first;
       nm = nm < prm.members_per_stage ? nm : prm.members_per_stage;
       for (int m = 0; m < nm; ++m) {
-        const uint32_t* w = wts + (size_t)m * prm.member_words;
+        const uint32_t* w = stage + (size_t)m * prm.member_words;
 #pragma unroll
         for (int r = 0; r < R; ++r) {
           if (any[r]) ysum[r] += Net::forward(w, feat[r], lane, prm.off);

@@ -501,6 +501,13 @@ static int run_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin
     int mps = budget / member_bytes;
     if (mps < 1) return set_error(TUNER_ETOOLARGE, "one packed member does not fit in LDS");
     mps = std::min(mps, sh.E);
+    // members that do not all fit are streamed through two half-size buffers if a
+    // member fits one half: the next stage loads while the current one is evaluated
+    bool double_buffer = false;
+    if (mps < sh.E && (budget / 2) / member_bytes >= 1) {
+      mps = (budget / 2) / member_bytes;
+      double_buffer = true;
+    }
     SweepParams sw{};
     sw.begin = begin;
     sw.count = count;
@@ -547,7 +554,9 @@ static int run_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin
     // the region after the space tables holds a stage of weights and doubles as sort
     // scratch for the candidate pool: make it large enough for a pool that is compacted
     // when it reaches 2 k + one queue unit, if the LDS allows
-    size_t region = (size_t)mps * member_bytes;
+    sw.double_buffer = double_buffer ? 1 : 0;
+    sw.stage_words = (uint32_t)(mps * sh.member_words);
+    size_t region = (size_t)mps * member_bytes * (double_buffer ? 2 : 1);
     if (mode == MODE_TOPK) {
       const size_t want = 8ull * host_next_pow2(2u * L.kp + super * (uint32_t)iter);
       if (want > region && want <= (size_t)budget) region = want;
