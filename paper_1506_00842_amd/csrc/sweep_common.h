@@ -60,7 +60,7 @@ struct SweepParams {
   uint32_t stage_words;       // words between the two buffers
   int32_t dynamic;            // units beyond a workgroup's first come from the queue counter (else strided)
   const uint32_t* live;       // optional list of chunks to sweep: chunk index | state << 30; its length is
-                              // hdr->n_live (chunks with no valid configuration are left out of top-k sweeps)
+                              // hdr->n_live (chunks with no valid configuration are left out)
   NetOffsets off;
   const DevSpace* space;      // in the workspace
   const uint32_t* packed;

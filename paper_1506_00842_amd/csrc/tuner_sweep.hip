@@ -332,19 +332,22 @@ static const Variant* find_variant(const Shape& sh) {
 // classify: for a long constrained range, the list of chunks the sweep has to visit.
 // A chunk whose rule parameters keep their digits over all its configurations (the
 // quotient index / stride is the same at both ends, hence throughout) is valid or
-// invalid as a whole.  Chunks without any valid configuration are left out of top-k
-// sweeps; the others carry their state, so that wholly valid chunks skip the per-lane
-// rule sums.  The order of the list does not matter to any result.
+// invalid as a whole.  Chunks without any valid configuration are left out of the list
+// (predict_all gets their +inf right here); the others carry their state, so that
+// wholly valid chunks skip the per-lane rule sums.  The order of the list does not
+// matter to any result.
 // ---------------------------------------------------------------------------
 struct ClassifyParams {
   uint64_t begin, count;
   uint32_t n_chunks, iter;
-  int32_t keep_invalid;       // predict_all writes +inf for them
+  float* pred;                // predict_all: wholly invalid chunks get their +inf (and mask 0) here
+  uint8_t* mask;
   uint32_t* live;
   WsHeader* hdr;
 };
 
 __global__ void __launch_bounds__(256) classify_kernel(const DevSpace sp, const ClassifyParams cp) {
+  __shared__ uint8_t s_state[256];
   const bool pow2 = sp.all_pow2 != 0;
   const uint32_t lane = threadIdx.x & 63;
   for (uint32_t base = blockIdx.x * blockDim.x; base < cp.n_chunks; base += gridDim.x * blockDim.x) {
@@ -365,12 +368,27 @@ __global__ void __launch_bounds__(256) classify_kernel(const DevSpace sp, const 
         }
       state = uniform ? (is_valid(sp, lo, pow2) ? CHUNK_ALL_VALID : CHUNK_ALL_INVALID) : CHUNK_MIXED;
     }
-    const bool keep = in && (state != CHUNK_ALL_INVALID || cp.keep_invalid);
+    const bool keep = in && state != CHUNK_ALL_INVALID;
     const unsigned long long bal = __ballot(keep);
     uint32_t pos = 0;
     if (lane == 0 && bal) pos = atomicAdd(&cp.hdr->n_live, (uint32_t)__popcll(bal));
     pos = __shfl(pos, 0);
     if (keep) cp.live[pos + __popcll(bal & ((1ull << lane) - 1ull))] = c | (state << 30);
+    if (cp.pred) {
+      // the block fills the outputs of its wholly invalid chunks, coalesced
+      __syncthreads();
+      s_state[threadIdx.x] = in ? (uint8_t)state : (uint8_t)CHUNK_MIXED;
+      __syncthreads();
+      for (uint32_t j = 0; j < blockDim.x; ++j) {
+        if (s_state[j] != CHUNK_ALL_INVALID) continue;
+        const uint64_t t0 = (uint64_t)(base + j) * cp.iter;
+        const uint64_t left = cp.count - t0 < (uint64_t)cp.iter ? cp.count - t0 : (uint64_t)cp.iter;
+        for (uint64_t x = threadIdx.x; x < left; x += blockDim.x) {
+          cp.pred[t0 + x] = __builtin_inff();
+          if (cp.mask) cp.mask[t0 + x] = 0;
+        }
+      }
+    }
   }
 }
 
@@ -543,7 +561,8 @@ static int run_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin
       cp.count = count;
       cp.n_chunks = n_chunks;
       cp.iter = (uint32_t)iter;
-      cp.keep_invalid = mode == MODE_ALL ? 1 : 0;
+      cp.pred = mode == MODE_ALL ? pred : nullptr;
+      cp.mask = mode == MODE_ALL ? mask : nullptr;
       cp.live = live;
       cp.hdr = hdr;
       hipLaunchKernelGGL(classify_kernel, dim3(std::min<uint32_t>(1024u, (n_chunks + 255u) / 256u)), dim3(256), 0,
