@@ -136,3 +136,46 @@ class Tuner:
         bt = torch.zeros(1, dtype=torch.float32, device=self.device)
         tuner_best_of(times.numel(), times, pos, bt, stream)
         return pos, bt
+
+
+class _TrainedModel:
+    """What Sweep needs of a model: n_members / widths / weights."""
+
+    def __init__(self, n_members, widths, weights):
+        self.n_members, self.widths, self.weights = n_members, list(widths), weights
+
+
+def tune(space, measure, initial_weights, n_train: int, m: int, n_members: int = 11, hidden: int = 30,
+         epochs: int = 1000, learning_rate: float = 0.125, momentum: float = 0.875, seed: int = 0,
+         device: str = "cuda:0"):
+    """The two-stage tuner of the paper's Section 5 around a caller-supplied measurement.
+
+    measure(indices uint64[n]) -> float32[n] execution times (a value that is not a finite
+    number > 0 marks a failed run); it stands for compiling and running the benchmark.
+    Steps: n_train random valid configurations -> their times -> bagged ensemble (n_members
+    networks P-hidden-1, network e trained without part e = every n_members-th sample) ->
+    sweep of the whole space, the m lowest predictions -> their times -> the fastest.
+    Every computation runs in the library; this function only moves the measurements in.
+    Returns a dict (best_index, best_time, candidates, candidate_times, weights, final_loss).
+    """
+    tn = Tuner(space, device)
+    idx_dev, found = tn.sample_valid(seed, n_train, min(1 << 24, 64 * n_train))
+    n = int(found.item())
+    if n == 0:
+        raise ValueError("no valid configuration found")
+    idx_dev = idx_dev[:n]
+    idx = idx_dev.cpu().numpy().view(np.uint32).astype(np.uint64)
+    times = np.ascontiguousarray(measure(idx), dtype=np.float32)
+    parts = (np.arange(n) % n_members).astype(np.int32) if n_members > 1 else np.full(n, -1, np.int32)
+    weights, loss = tn.train(n_members, hidden, idx_dev, times, parts, initial_weights, epochs,
+                             learning_rate, momentum)
+    model = _TrainedModel(n_members, [tn.n_params, hidden, 1], weights.cpu().numpy())
+    sw = Sweep(space, model, m, device)
+    sw.topk()
+    _, cand = sw.topk_host()
+    cand_times = np.ascontiguousarray(measure(cand), dtype=np.float32)
+    pos, best_time = tn.best_of(torch.from_numpy(cand_times).to(tn.device))
+    pos = int(pos.item())
+    return {"best_index": int(cand[pos]) if pos >= 0 else None, "best_time": float(best_time.item()),
+            "candidates": cand, "candidate_times": cand_times, "weights": model.weights,
+            "final_loss": loss[:, -1].cpu().numpy()}

@@ -373,3 +373,27 @@ def test_two_stage_tuner_end_to_end():
     best_valid = all_t[(ov == 1) & (all_t > 0)].min()
     say(f"  tuner result {obt:.3e} s vs global optimum {best_valid:.3e} s: slowdown {obt / best_valid:.3f}")
     assert obt / best_valid < 1.5
+
+
+def test_tune_function_runs_the_whole_tuner():
+    """api.tune on the stereo space (2,359,296 configurations) with the settings the paper
+    uses for its large spaces (3000 training configurations, M = 300)."""
+    from paper_1506_00842_amd.api import tune
+    sp = wl.paper_stereo().space
+    bm = SyntheticBenchmark(sp, 91)
+    calls = []
+
+    def measure(indices):
+        calls.append(len(indices))
+        return bm.times(indices)
+
+    res = tune(sp, measure, initial_weights(11, sp.n_params, 30, 910), n_train=3000, m=300, epochs=300, seed=91)
+    assert calls == [3000, 300]
+    assert res["best_index"] is not None and np.all(np.isfinite(res["final_loss"]))
+    assert res["best_time"] == np.min(res["candidate_times"][res["candidate_times"] > 0])
+    # against the best of 50,000 random valid configurations (the paper's yardstick for the
+    # spaces it could not search exhaustively)
+    ref = bm.times(oracle.sample_valid(sp, 92, 50_000, 400_000))
+    best_random = ref[ref > 0].min()
+    say(f"  tuner {res['best_time']:.4e} s vs best of 50,000 random {best_random:.4e} s: ratio {res['best_time'] / best_random:.3f}")
+    assert res["best_time"] < 1.25 * best_random
