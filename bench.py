@@ -25,7 +25,7 @@ PEAK_HBM_GBS = 8000.0
 # HBM bytes per sweep launch from rocprofv3 FETCH_SIZE / WRITE_SIZE (KiB per dispatch, scaled
 # by the factors a plain 1 GiB copy gives in the same run: 2.000 and 1.000); see
 # profiles/sweep_kernel_f32mfma_cfg3.md.  Not measurable from inside this script.
-TRAFFIC_BYTES = {("cfg3", "topk", "f32-mfma"): (9396.23 * 2.0 + 22627.98) * 1024.0,
+TRAFFIC_BYTES = {("cfg3", "topk", "f32-mfma"): (1209.92 * 2.0 + 2550.7) * 1024.0,
                  ("cfg3", "all", "f32-mfma"): 525320.0 * 1024.0}
 
 

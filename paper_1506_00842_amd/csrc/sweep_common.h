@@ -56,6 +56,8 @@ struct SweepParams {
   float inv_members;          // 1 / n_members, rounded once from double
   uint32_t cap, kp;           // pool capacity per workgroup, k rounded up to a power of two
   uint32_t lds_entries;       // keys that fit the LDS region after the space tables (weights / sort scratch)
+  uint32_t lds_pool_entries;  // > 0: the candidate pool lives in LDS (a power of two of keys) ...
+  uint32_t lds_pool_offset;   // ... at this byte offset of the dynamic LDS
   int32_t double_buffer;      // two stage buffers in LDS, filled by LDS-direct loads during the evaluation
   uint32_t stage_words;       // words between the two buffers
   int32_t dynamic;            // units beyond a workgroup's first come from the queue counter (else strided)

@@ -39,7 +39,14 @@ __global__ void __launch_bounds__(NW * 64) sweep_kernel(const SweepParams prm) {
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave_u = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave index, known uniform
   const int c = kTile == 32 ? (lane & 31) : lane, h = kTile == 32 ? (lane >> 5) : 0;
-  unsigned long long* pool = prm.pools + (size_t)blockIdx.x * prm.cap;
+  // candidate pool: in LDS behind the weights when there is room for 2 k + one queue
+  // unit of keys (then no candidate ever travels to HBM and back, and a compaction
+  // leaves the weights alone); otherwise in the workgroup's slice of the workspace
+  // (two pointers and explicit branches: one pointer that may be either would make every
+  // access a flat one)
+  unsigned long long* gpool = prm.pools + (size_t)blockIdx.x * prm.cap;
+  unsigned long long* lpool = reinterpret_cast<unsigned long long*>(smem + prm.lds_pool_offset);
+  const bool pool_in_lds = prm.lds_pool_entries > 0;
 
   {
     const uint32_t* src = reinterpret_cast<const uint32_t*>(prm.space);
@@ -86,7 +93,9 @@ __global__ void __launch_bounds__(NW * 64) sweep_kernel(const SweepParams prm) {
   const uint32_t super_iter = (uint32_t)prm.super * kIter;
   // pools are compacted while they still fit the LDS sort scratch, if that leaves room
   uint32_t eff_cap = prm.cap;
-  {
+  if (pool_in_lds) {
+    eff_cap = prm.lds_pool_entries;
+  } else {
     uint32_t lds_pow2 = 1;
     while (lds_pow2 * 2 <= lds_entries) lds_pow2 *= 2;
     if (lds_pow2 < eff_cap && lds_pow2 >= 2u * prm.kp + super_iter) eff_cap = lds_pow2;
@@ -130,13 +139,19 @@ __global__ void __launch_bounds__(NW * 64) sweep_kernel(const SweepParams prm) {
       // pool nearly full: keep its k smallest keys, lower the thresholds
       const uint32_t n = s_cnt;
       const uint32_t n2 = next_pow2(n);
-      for (uint32_t x = n + tid; x < n2; x += kThreads) pool[x] = kKeyMax;
-      __syncthreads();
-      sort_pool(pool, n2, lds_keys, lds_entries, tid, kThreads);
-      if (prm.n_stages == 1 && n2 <= lds_entries) load_stage(0);   // scratch held the weights
+      if (pool_in_lds) {
+        for (uint32_t x = n + tid; x < n2; x += kThreads) lpool[x] = kKeyMax;
+        __syncthreads();
+        bitonic_sort(lpool, n2, tid, kThreads);
+      } else {
+        for (uint32_t x = n + tid; x < n2; x += kThreads) gpool[x] = kKeyMax;
+        __syncthreads();
+        sort_pool(gpool, n2, lds_keys, lds_entries, tid, kThreads);
+        if (prm.n_stages == 1 && n2 <= lds_entries) load_stage(0);   // scratch held the weights
+      }
       if (tid == 0) {
         if (n >= (uint32_t)prm.k) {
-          const unsigned long long t = pool[prm.k - 1];
+          const unsigned long long t = pool_in_lds ? lpool[prm.k - 1] : gpool[prm.k - 1];
           s_tau_local = t;
           atomicMin(&prm.hdr->tau, t);
           if (t < s_tau) s_tau = t;
@@ -244,7 +259,11 @@ __global__ void __launch_bounds__(NW * 64) sweep_kernel(const SweepParams prm) {
           uint32_t base = 0;
           if (lane == 0) base = atomicAdd(&s_cnt, (uint32_t)__popcll(bal));
           base = __shfl(base, 0);
-          if (pass) pool[base + __popcll(bal & ((1ull << lane) - 1ull))] = key;
+          if (pass) {
+            const uint32_t at = base + __popcll(bal & ((1ull << lane) - 1ull));
+            if (pool_in_lds) lpool[at] = key;
+            else gpool[at] = key;
+          }
         }
       }
     }
@@ -257,9 +276,16 @@ __global__ void __launch_bounds__(NW * 64) sweep_kernel(const SweepParams prm) {
     const uint32_t n = s_cnt;
     uint32_t n2 = next_pow2(n);
     n2 = n2 < prm.kp ? prm.kp : n2;
-    for (uint32_t x = n + tid; x < n2; x += kThreads) pool[x] = kKeyMax;
-    __syncthreads();
-    sort_pool(pool, n2, lds_keys, lds_entries, tid, kThreads);
+    if (pool_in_lds) {
+      for (uint32_t x = n + tid; x < n2; x += kThreads) lpool[x] = kKeyMax;
+      __syncthreads();
+      bitonic_sort(lpool, n2, tid, kThreads);
+      for (uint32_t x = tid; x < prm.kp; x += kThreads) gpool[x] = lpool[x];
+    } else {
+      for (uint32_t x = n + tid; x < n2; x += kThreads) gpool[x] = kKeyMax;
+      __syncthreads();
+      sort_pool(gpool, n2, lds_keys, lds_entries, tid, kThreads);
+    }
   }
 }
 

@@ -110,7 +110,7 @@ __global__ void __launch_bounds__(256) prep_kernel(const DevSpace sp, const Prep
 // outputs.  merge_kernel: one pair per workgroup, in place in global memory, for
 // lists too long for LDS.
 // ---------------------------------------------------------------------------
-constexpr uint32_t kWaveMergeMaxKp = 1024;   // lists up to this long are merged one pair per wave
+constexpr uint32_t kWaveMergeMaxKp = 256;    // lists up to this long are merged one pair per wave
 
 struct MergeParams {
   unsigned long long* pools;
@@ -581,7 +581,23 @@ static int run_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin
       if (want > region && want <= (size_t)budget) region = want;
     }
     sw.lds_entries = (uint32_t)(region / 8);
-    const size_t lds = (size_t)kSpaceBytes + region;
+    size_t lds = (size_t)kSpaceBytes + region;
+    // resident ensembles that leave room keep the candidate pool in LDS too
+    sw.lds_pool_entries = 0;
+    sw.lds_pool_offset = 0;
+    if (mode == MODE_TOPK && sw.n_stages == 1 && sw.dynamic) {   // short ranges: one pool fill at most, the global pool is as good
+      const size_t weights_bytes = ((size_t)mps * member_bytes + 15) / 16 * 16;
+      const size_t room = (size_t)budget > weights_bytes ? (size_t)budget - weights_bytes : 0;
+      // the smallest pool that takes 2 k keys and one queue unit: small pools are sorted
+      // more often but much faster, and tighten the threshold sooner
+      const uint32_t entries = host_next_pow2(2u * L.kp + super * (uint32_t)iter);
+      if ((size_t)entries * 8 <= room) {
+        sw.lds_pool_entries = entries;
+        sw.lds_pool_offset = (uint32_t)(kSpaceBytes + weights_bytes);
+        sw.lds_entries = (uint32_t)(weights_bytes / 8);
+        lds = (size_t)kSpaceBytes + weights_bytes + (size_t)entries * 8;
+      }
+    }
     TUNER_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(var->fn),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
