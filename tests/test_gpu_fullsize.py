@@ -218,3 +218,53 @@ def test_large_2_27_other_nets_full(net):
     S = parity.scale_of(ry)
     assert np.all(np.abs(gv.astype(np.float64) - ry) <= tol * np.maximum(np.abs(ry), S))
     say(f"  {net}: worst {worst_all:.3f} x tol({tol:g})")
+
+
+@pytest.mark.parametrize("radices,begin,count", [
+    ([8, 8, 8, 8, 4, 4, 4, 4, 4, 2, 2, 2, 2, 2], 12345, (1 << 24) + 777),          # powers of two, ragged range
+    ([8, 5, 8, 3, 4, 4, 3, 4, 4, 2, 2, 3, 2, 2], 1000003, (1 << 24) + 12345),      # multiply-shift decoder
+])
+def test_long_range_with_rules_on_low_parameters(radices, begin, count):
+    """A long sweep visits a list of live chunks made from each chunk's two end points.
+    Here the range starts off any chunk boundary and the rules touch high, middle and
+    low parameters, so chunks are wholly invalid, wholly valid or mixed: the mask of the
+    whole range against the oracle's (integer work only), the top-k against the exact
+    selection from the GPU's own predictions, and sampled predictions against the oracle."""
+    from paper_1506_00842_amd.api import Sweep
+    values = [[float(1 << j) for j in range(r)] if r > 2 else [0.0, 1.0] for r in radices]
+    scales = [wl.SCALE_LOG2 if r > 2 else wl.SCALE_LINEAR for r in radices]
+    total = sum(radices)
+    off = np.concatenate([[0], np.cumsum(radices)])[:-1]
+    terms = np.zeros((4, total), np.int32)
+    for p in (0, 1):                                   # high: d0 + d1 <= 9
+        terms[0, off[p]:off[p] + radices[p]] = np.arange(radices[p])
+    terms[1, off[2]:off[2] + radices[2]] = np.arange(radices[2])      # high: d2 <= d3 + 4
+    terms[1, off[3]:off[3] + radices[3]] = -np.arange(radices[3])
+    for p in (6, 7):                                   # middle (strides around one chunk): d6 + d7 <= 4
+        terms[2, off[p]:off[p] + radices[p]] = np.arange(radices[p])
+    for p in (10, 11, 13):                             # low (inside a tile): d10 + d11 + d13 <= 2
+        terms[3, off[p]:off[p] + radices[p]] = np.arange(radices[p])
+    sp = wl.Space("mixed-chunks", values, scales, terms, np.array([9, 4, 4, 2], np.int64))
+    assert begin + count <= sp.n_configs
+    w = wl.Workload("mixed-chunks", sp, wl.make_model([14, 64, 64, 1], 2, 77), 500)
+    sw = Sweep(sp, w.model, w.k)
+    sw.topk(begin, count)
+    pred, mask = sw.predict_all(begin, count)
+    torch.cuda.synchronize()
+    _, ov, _ = oracle.predict_range(sp, None, begin, count, threads=THREADS, want_yhat=False)
+    gm = mask.cpu().numpy()
+    assert np.array_equal(gm, ov)
+    say(f"  {int(ov.sum())} of {count} valid")
+    assert 0.05 < ov.mean() < 0.95
+    assert bool(torch.all(torch.isposinf(pred[~mask.bool()])))
+    gv, gi = sw.topk_host()
+    ev, ei = exact_topk_of(pred, mask, begin, w.k)
+    assert np.array_equal(gi, ei) and np.array_equal(gv, ev)
+    # values: windows of the long run's own output against the oracle
+    st = wl.Stream(5)
+    for t0 in [0, count - 3000] + [int(v) for v in st.integers(6, count - 3000)]:
+        oy, ov2, _ = oracle.predict_range(sp, w.model, begin + t0, 3000, threads=THREADS)
+        assert np.array_equal(gm[t0:t0 + 3000], ov2)
+        parity.check_predictions(pred[t0:t0 + 3000].cpu().numpy(), oy, ov2)
+    ry, rv = oracle.predict_indices(sp, w.model, gi, threads=THREADS)
+    assert rv.all()
