@@ -7,7 +7,10 @@ merge) over the whole synthetic space, inputs resident in HBM.  Default
 workload: the 2^27-configuration space with 4 networks 14-64-64-1, k = 1000
 (the configuration the headline metric and target are quoted on).
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line: metric, value (swept configurations per second), ms_per_step,
+config, roofline (the sweep kernel against the fp32 matrix peak, from HIP events recorded
+by the library on the launch stream), other_nets, cpu_baseline (the CPU oracle on the
+host cores, on a bounded sample of the same workload).
 """
 from __future__ import annotations
 
@@ -23,8 +26,8 @@ sys.path.insert(0, ROOT)
 PEAK_FP32_MATRIX_TFLOPS = 157.3   # MI355X published dense fp32 matrix (= fp32 vector) peak
 PEAK_HBM_GBS = 8000.0
 # HBM bytes per sweep launch from rocprofv3 FETCH_SIZE / WRITE_SIZE (KiB per dispatch, scaled
-# by the factors a plain 1 GiB copy gives in the same run: 2.000 and 1.000); see
-# profiles/sweep_kernel_f32mfma_cfg3.md.  Not measurable from inside this script.
+# by the factors a plain 1 GiB copy gives in the same run: 2.000 and 1.000).  Not
+# measurable from inside this script; the summary of those runs is kept under profiles/.
 TRAFFIC_BYTES = {("cfg3", "topk", "f32-mfma"): (1209.92 * 2.0 + 2550.7) * 1024.0,
                  ("cfg3", "all", "f32-mfma"): 525320.0 * 1024.0}
 
