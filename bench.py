@@ -264,6 +264,10 @@ def main():
     ms_per_step = 1e3 * dt / args.steps
     n_valid = w.n_valid if w.n_valid >= 0 else None
     flop_per_cfg = 2 * m.macs_per_config
+    # layer-1 share of the parameters that are constant over a tile of 32 configurations:
+    # computed once per tile, i.e. 31/32 of those multiply-adds are never executed
+    n_hoisted = T.tuner_hoisted_parameters(sw.space, sw.model)
+    executed_flop_per_cfg = flop_per_cfg - 2.0 * m.n_members * m.widths[1] * n_hoisted * 31.0 / 32.0
     launches_per_step = n_launch / args.steps
     kernel_ms = sweep_ms / max(n_launch, 1)
     roof = None
@@ -278,6 +282,8 @@ def main():
                 "kernel": "sweep_kernel (fp32 MFMA 32x32x2)", "kernel_ms": kernel_ms,
                 "launches_per_step": launches_per_step,
                 "flop_per_config": flop_per_cfg, "evaluated_configs_per_launch": n_valid / launches_per_step,
+                "hoisted_parameters": n_hoisted, "executed_flop_per_config": executed_flop_per_cfg,
+                "frac_executed": achieved * executed_flop_per_cfg / flop_per_cfg / PEAK_FP32_MATRIX_TFLOPS,
                 "sigmoids_per_config": m.sigmoids_per_config}
     out = {
         "metric": "predicted configs/sec (decode+MLP ensemble+top-k)" if args.mode == "topk"

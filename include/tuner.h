@@ -143,6 +143,18 @@ int tuner_space_decode_device_arith(const tuner_space* space, uint64_t index, in
 size_t tuner_workspace_bytes(const tuner_space* space, const tuner_model* model, int32_t k);
 
 /*
+ * How a range sweep of this model over this space evaluates layer 1 (host only).
+ * Consecutive configurations share all but their last few parameter values (the space
+ * is a Cartesian product, Section 5.1): the parameters whose stride is a multiple of 32
+ * have one value per tile of 32 configurations, and the fp32 matrix network computes
+ * their share of the layer-1 pre-activations once per tile instead of once per
+ * configuration.  *n_hoisted receives the number of such parameters this library
+ * treats that way (0: none; always 0 for the other network evaluations and for
+ * tuner_predict_indices).
+ */
+int tuner_hoisted_parameters(const tuner_space* space, const tuner_model* model, int32_t* n_hoisted);
+
+/*
  * Sweep of indices [index_begin, index_begin + index_count) and selection of
  * the k valid configurations with the smallest predictions, ordered by
  * (prediction, then index), ascending (Section 5.3).

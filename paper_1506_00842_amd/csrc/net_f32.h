@@ -25,6 +25,85 @@
 
 namespace tuner {
 
+// sigma on 16 accumulator registers, in three passes (exp2, +1, rcp) so that no
+// instruction waits on the transcendental that precedes it
+__device__ __forceinline__ void sigmoid16(floatx16& a) {
+#pragma unroll
+  for (int v = 0; v < 16; ++v) a[v] = __builtin_amdgcn_exp2f(a[v]);
+#pragma unroll
+  for (int v = 0; v < 16; ++v) a[v] = 1.0f + a[v];
+#pragma unroll
+  for (int v = 0; v < 16; ++v) a[v] = __builtin_amdgcn_rcpf(a[v]);
+}
+
+// Everything after the layer-1 pre-activations (scaled by -log2 e) are in a1: sigmoid,
+// second hidden layer if any, output layer.  Returns the lane's share of the output.
+template <int NT1, int NT2>
+__device__ __forceinline__ float f32_after_layer1(const float* __restrict__ w, floatx16 (&a1)[NT1], int lane,
+                                                  const NetOffsets& o) {
+  const int h = lane >> 5;
+  // fp32 MFMA and VALU work do not overlap on a SIMD, so nothing is gained by
+  // interleaving the sigmoid with the matrix instructions
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int t = 0; t < NT1; ++t) sigmoid16(a1[t]);
+  __builtin_amdgcn_sched_barrier(0);
+
+  float part = 0.0f;
+  if constexpr (NT2 > 0) {
+    floatx16 a2[NT2];
+    const float4* b2 = reinterpret_cast<const float4*>(w + o.b2);
+#pragma unroll
+    for (int u = 0; u < NT2; ++u)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const float4 b = b2[(u * 4 + g) * 2 + h];
+        a2[u][4 * g + 0] = b.x; a2[u][4 * g + 1] = b.y; a2[u][4 * g + 2] = b.z; a2[u][4 * g + 3] = b.w;
+      }
+    const float4* w2 = reinterpret_cast<const float4*>(w + o.w2);
+#pragma unroll
+    for (int t = 0; t < NT1; ++t)
+#pragma unroll
+      for (int g = 0; g < 4; ++g)
+#pragma unroll
+        for (int u = 0; u < NT2; ++u) {
+          const float4 a = w2[((u * NT1 + t) * 4 + g) * 64 + lane];
+          a2[u] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, a1[t][4 * g + 0], a2[u], 0, 0, 0);
+          a2[u] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, a1[t][4 * g + 1], a2[u], 0, 0, 0);
+          a2[u] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, a1[t][4 * g + 2], a2[u], 0, 0, 0);
+          a2[u] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, a1[t][4 * g + 3], a2[u], 0, 0, 0);
+        }
+    const float4* wo = reinterpret_cast<const float4*>(w + o.wo);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int u = 0; u < NT2; ++u) sigmoid16(a2[u]);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int u = 0; u < NT2; ++u)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const float4 q = wo[(u * 4 + g) * 2 + h];
+        part = fmaf(q.x, a2[u][4 * g + 0], part);
+        part = fmaf(q.y, a2[u][4 * g + 1], part);
+        part = fmaf(q.z, a2[u][4 * g + 2], part);
+        part = fmaf(q.w, a2[u][4 * g + 3], part);
+      }
+  } else {
+    const float4* wo = reinterpret_cast<const float4*>(w + o.wo);
+#pragma unroll
+    for (int t = 0; t < NT1; ++t)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const float4 q = wo[(t * 4 + g) * 2 + h];
+        part = fmaf(q.x, a1[t][4 * g + 0], part);
+        part = fmaf(q.y, a1[t][4 * g + 1], part);
+        part = fmaf(q.z, a1[t][4 * g + 2], part);
+        part = fmaf(q.w, a1[t][4 * g + 3], part);
+      }
+  }
+  return part;
+}
+
 template <int KS1, int NT1, int NT2>
 struct F32Net {
   static constexpr int kTile = 32;
@@ -34,8 +113,9 @@ struct F32Net {
   // after it decodes to the constant 1 that multiplies the bias column (the prep kernel
   // points that slot of the table at the constant)
   static constexpr bool kBiasInput = true;
+  static constexpr bool kHoist = false;
   static __device__ __forceinline__ void load_features(const DevSpace& sp, uint32_t i, int lane, bool pow2,
-                                                       Feat& f) {
+                                                       const NetOffsets&, Feat& f) {
     const int h = lane >> 5;
     if (pow2) {
 #pragma unroll
@@ -48,15 +128,6 @@ struct F32Net {
   static __device__ __forceinline__ void zero_features(Feat& f) {
 #pragma unroll
     for (int s = 0; s < KS1; ++s) f.x[s] = 0.0f;
-  }
-
-  static __device__ __forceinline__ void sigmoid16(floatx16& a) {
-#pragma unroll
-    for (int v = 0; v < 16; ++v) a[v] = __builtin_amdgcn_exp2f(a[v]);
-#pragma unroll
-    for (int v = 0; v < 16; ++v) a[v] = 1.0f + a[v];
-#pragma unroll
-    for (int v = 0; v < 16; ++v) a[v] = __builtin_amdgcn_rcpf(a[v]);
   }
 
   static __device__ __forceinline__ float forward(const uint32_t* __restrict__ wm, const Feat& f, int lane,
@@ -89,67 +160,7 @@ struct F32Net {
         a1[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, f.x[KS1 - 1], a1[t], 0, 0, 0);
       }
     }
-    // sigmoid in three passes (exp2, +1, rcp) so that no instruction waits on the
-    // transcendental that precedes it; fp32 MFMA and VALU work do not overlap on a
-    // SIMD, so nothing is gained by interleaving them
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int t = 0; t < NT1; ++t) sigmoid16(a1[t]);
-    __builtin_amdgcn_sched_barrier(0);
-
-    float part = 0.0f;
-    if constexpr (NT2 > 0) {
-      floatx16 a2[NT2];
-      const float4* b2 = reinterpret_cast<const float4*>(w + o.b2);
-#pragma unroll
-      for (int u = 0; u < NT2; ++u)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const float4 b = b2[(u * 4 + g) * 2 + h];
-          a2[u][4 * g + 0] = b.x; a2[u][4 * g + 1] = b.y; a2[u][4 * g + 2] = b.z; a2[u][4 * g + 3] = b.w;
-        }
-      const float4* w2 = reinterpret_cast<const float4*>(w + o.w2);
-#pragma unroll
-      for (int t = 0; t < NT1; ++t)
-#pragma unroll
-        for (int g = 0; g < 4; ++g)
-#pragma unroll
-          for (int u = 0; u < NT2; ++u) {
-            const float4 a = w2[((u * NT1 + t) * 4 + g) * 64 + lane];
-            a2[u] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, a1[t][4 * g + 0], a2[u], 0, 0, 0);
-            a2[u] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, a1[t][4 * g + 1], a2[u], 0, 0, 0);
-            a2[u] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, a1[t][4 * g + 2], a2[u], 0, 0, 0);
-            a2[u] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, a1[t][4 * g + 3], a2[u], 0, 0, 0);
-          }
-      const float4* wo = reinterpret_cast<const float4*>(w + o.wo);
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int u = 0; u < NT2; ++u) sigmoid16(a2[u]);
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int u = 0; u < NT2; ++u)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const float4 q = wo[(u * 4 + g) * 2 + h];
-          part = fmaf(q.x, a2[u][4 * g + 0], part);
-          part = fmaf(q.y, a2[u][4 * g + 1], part);
-          part = fmaf(q.z, a2[u][4 * g + 2], part);
-          part = fmaf(q.w, a2[u][4 * g + 3], part);
-        }
-    } else {
-      const float4* wo = reinterpret_cast<const float4*>(w + o.wo);
-#pragma unroll
-      for (int t = 0; t < NT1; ++t)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const float4 q = wo[(t * 4 + g) * 2 + h];
-          part = fmaf(q.x, a1[t][4 * g + 0], part);
-          part = fmaf(q.y, a1[t][4 * g + 1], part);
-          part = fmaf(q.z, a1[t][4 * g + 2], part);
-          part = fmaf(q.w, a1[t][4 * g + 3], part);
-        }
-    }
-    return part;
+    return f32_after_layer1<NT1, NT2>(w, a1, lane, o);
   }
 };
 

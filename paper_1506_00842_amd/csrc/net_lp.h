@@ -91,8 +91,9 @@ struct LpNet {
       }
     }
   }
+  static constexpr bool kHoist = false;
   static __device__ __forceinline__ void load_features(const DevSpace& sp, uint32_t i, int lane, bool pow2,
-                                                       Feat& f) {
+                                                       const NetOffsets&, Feat& f) {
     if (pow2) load_features_t<true>(sp, i, lane >> 5, f);
     else load_features_t<false>(sp, i, lane >> 5, f);
   }

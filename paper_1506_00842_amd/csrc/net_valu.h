@@ -20,8 +20,9 @@ struct ValuNet {
   struct Feat { float x[PMAX]; };
 
   static constexpr bool kBiasInput = false;
+  static constexpr bool kHoist = false;
   static __device__ __forceinline__ void load_features(const DevSpace& sp, uint32_t i, int lane, bool pow2,
-                                                       Feat& f) {
+                                                       const NetOffsets&, Feat& f) {
     if (pow2) {
 #pragma unroll
       for (int p = 0; p < PMAX; ++p) f.x[p] = feature_at_t<true>(sp, p, i);   // 0 past the last parameter

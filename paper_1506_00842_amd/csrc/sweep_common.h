@@ -42,12 +42,18 @@ struct Shape {
   int o_w1, o_w2, o_b1, o_b2, o_wo;
   int member_words;           // multiple of 4
   int raw_member_floats;
+  // fp32 matrix network with the high parameters' layer-1 share computed once per tile
+  int hoist;                  // 0 / 1
+  int p0;                     // parameters 0 .. p0-1 are constant over a tile of 32 configurations
+  int n_high4;                // p0 rounded up to a multiple of 4
+  int o_wh;                   // their weights, [n_high4 + 1][NT1 * 32]
 };
 
-struct NetOffsets { int w1, w2, b1, b2, wo, h1, h2; };   // word offsets; real hidden widths
+struct NetOffsets { int w1, w2, b1, b2, wo, h1, h2, wh, p0, n_high4; };   // word offsets; real hidden widths; hoisting
 
 struct SweepParams {
   uint64_t begin, count;
+  uint32_t head;               // positions of the range before the caller's first configuration (masked)
   uint32_t n_chunks, n_units;  // chunks of waves*R*tile configurations; queue units of `super` chunks
   int32_t super;
   int32_t r_used;              // tiles per wave and chunk actually used (1 .. the variant's R)
@@ -58,6 +64,7 @@ struct SweepParams {
   uint32_t lds_entries;       // keys that fit the LDS region after the space tables (weights / sort scratch)
   uint32_t lds_pool_entries;  // > 0: the candidate pool lives in LDS (a power of two of keys) ...
   uint32_t lds_pool_offset;   // ... at this byte offset of the dynamic LDS
+  uint32_t hoist_offset;      // byte offset in the dynamic LDS of the per-wave scratch of the hoisting network
   int32_t double_buffer;      // two stage buffers in LDS, filled by LDS-direct loads during the evaluation
   uint32_t stage_words;       // words between the two buffers
   int32_t dynamic;            // units beyond a workgroup's first come from the queue counter (else strided)
@@ -78,6 +85,7 @@ struct Variant { int net, KS, NT1, NT2, R, waves, tile; SweepFn fn; };
 
 // Lookups implemented next to the instantiations (one translation unit per family).
 const Variant* find_variant_f32(int KS, int NT1, int NT2);
+const Variant* find_variant_f32h(int KSL, int NT1, int NT2);
 const Variant* find_variant_lp(int net, int KS, int NT1, int NT2);
 const Variant* find_variant_valu(int KS, int NT1, int NT2);
 

@@ -10,7 +10,7 @@
 //                                                 configuration is shared by the lane pair
 //                                                 (lane, lane ^ 32)) or 64 (one per lane)
 //   struct Feat                                   per-tile network input registers
-//   static void load_features(sp, index, lane, pow2, Feat&)
+//   static void load_features(sp, index, lane, pow2, offsets, Feat&)
 //   static void zero_features(Feat&)
 //   static float forward(const uint32_t* member_lds, const Feat&, int lane, const NetOffsets&)
 //        -> the lane's share of the member's output (both halves of a lane pair
@@ -81,6 +81,13 @@ __global__ void __launch_bounds__(NW * 64) sweep_kernel(const SweepParams prm) {
     }
   };
   const bool double_buffer = prm.double_buffer != 0;
+  // per-wave scratch of the hoisting network: the tiles' high features, then one z_high vector
+  float* hoist_xs = nullptr;
+  float* hoist_zs = nullptr;
+  if constexpr (Net::kHoist) {
+    hoist_xs = reinterpret_cast<float*>(smem + prm.hoist_offset) + (size_t)wave_u * (R * 32 + Net::kScratchZ);
+    hoist_zs = hoist_xs + R * 32;
+  }
   if (prm.n_stages == 1) load_stage(0);
   const float bo_sum = prm.hdr->bo_sum;
   const bool pow2 = prm.space->all_pow2 != 0;
@@ -187,7 +194,7 @@ __global__ void __launch_bounds__(NW * 64) sweep_kernel(const SweepParams prm) {
       uint32_t i = (uint32_t)(prm.begin + t0) + (uint32_t)c;   // any 32-bit index decodes safely
       if (prm.index_list) i = (uint32_t)c < left ? prm.index_list[t0 + (uint32_t)c] : 0u;
       idx[r] = i;
-      bool v = (uint32_t)c < left;
+      bool v = (uint32_t)c < left && t0 + (uint32_t)c >= prm.head;
       if (state == CHUNK_MIXED) {
         for (int cc = 0; cc < n_constraints; ++cc) {
           int ps;
@@ -204,8 +211,12 @@ __global__ void __launch_bounds__(NW * 64) sweep_kernel(const SweepParams prm) {
       ok[r] = v;
       any[r] = __ballot(v) != 0ull;
       ysum[r] = 0.0f;
-      if (any[r]) Net::load_features(sp, i, lane, pow2, feat[r]);
-      else Net::zero_features(feat[r]);
+      if (any[r]) {
+        Net::load_features(sp, i, lane, pow2, prm.off, feat[r]);
+        if constexpr (Net::kHoist) Net::load_high(sp, i, lane, pow2, prm.off, hoist_xs + r * 32);
+      } else {
+        Net::zero_features(feat[r]);
+      }
     }
 
     // ---- ensemble
@@ -232,7 +243,10 @@ __global__ void __launch_bounds__(NW * 64) sweep_kernel(const SweepParams prm) {
         const uint32_t* w = stage + (size_t)m * prm.member_words;
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-          if (any[r]) ysum[r] += Net::forward(w, feat[r], lane, prm.off);
+          if (any[r]) {
+            if constexpr (Net::kHoist) ysum[r] += Net::forward(w, feat[r], lane, prm.off, hoist_xs + r * 32, hoist_zs);
+            else ysum[r] += Net::forward(w, feat[r], lane, prm.off);
+          }
         }
       }
     }
@@ -247,7 +261,7 @@ __global__ void __launch_bounds__(NW * 64) sweep_kernel(const SweepParams prm) {
         const uint64_t t0 = (uint64_t)chunk * kIter + (uint32_t)((wave_u * r_used + r) * kTile);
         const uint32_t left =
             (r < r_used && t0 < prm.count) ? (uint32_t)min((uint64_t)kTile, prm.count - t0) : 0u;
-        if (h == 0 && (uint32_t)c < left) {
+        if (h == 0 && (uint32_t)c < left && t0 + (uint32_t)c >= prm.head) {
           prm.pred[t0 + (uint32_t)c] = ok[r] ? y : __builtin_inff();
           if (prm.mask) prm.mask[t0 + (uint32_t)c] = ok[r] ? 1 : 0;
         }

@@ -24,6 +24,7 @@
 #include <vector>
 
 #include "net_f32.h"
+#include "net_f32h.h"
 #include "net_lp.h"
 #include "net_valu.h"
 #include "sweep_common.h"
@@ -63,6 +64,7 @@ __global__ void __launch_bounds__(256) prep_kernel(const DevSpace sp, const Prep
     if (sh.net == NET_BF16) word = pack_word_lp<__bf16>(sh, raw, q);
     else if (sh.net == NET_F16X2) word = pack_word_lp<_Float16>(sh, raw, q);
     else if (sh.net == NET_F32_VALU) word = __float_as_uint(pack_word_valu(sh, raw, q));
+    else if (sh.hoist) word = __float_as_uint(pack_word_f32h(sh, raw, q));
     else word = __float_as_uint(pack_word_f32(sh, raw, q));
     pp.packed[x] = word;
   }
@@ -73,7 +75,7 @@ __global__ void __launch_bounds__(256) prep_kernel(const DevSpace sp, const Prep
     for (uint32_t x = gtid; x < sizeof(DevSpace) / 4; x += gsize) dst[x] = src[x];
     // the fp32 matrix network reads its bias column's constant 1 as the feature of the
     // slot after the last parameter (same thread as the plain copy of that word)
-    if (sh.net == NET_F32_MFMA) {
+    if (sh.net == NET_F32_MFMA && !sh.hoist) {
       const uint32_t word = (uint32_t)((const char*)&sp.pa[sh.P].lut_off4 - (const char*)&sp) / 4u;
       if (gtid == word % gsize) pp.space_out->pa[sh.P].lut_off4 = 4u * (uint32_t)kLutOne;
     }
@@ -258,7 +260,7 @@ finalize_kernel(const unsigned long long* list, int32_t k, float* values, uint32
 // ---------------------------------------------------------------------------
 static int round_up(int v, int m) { return (v + m - 1) / m * m; }
 
-static int make_shape(const tuner_space* sp, const tuner_model* m, Shape* sh) {
+static int make_shape(const tuner_space* sp, const tuner_model* m, Shape* sh, bool allow_hoist = false) {
   if (!m->widths || !m->weights_dev) return set_error(TUNER_EINVAL, "null model arrays");
   if (m->n_members < 1) return set_error(TUNER_EINVAL, "n_members < 1");
   if (m->n_layers != 2 && m->n_layers != 3) return set_error(TUNER_EINVAL, "n_layers must be 2 or 3");
@@ -289,7 +291,32 @@ static int make_shape(const tuner_space* sp, const tuner_model* m, Shape* sh) {
   if (sh->NT2 && sh->NT1 != sh->NT2) sh->NT1 = sh->NT2 = sh->NT1 > sh->NT2 ? sh->NT1 : sh->NT2;
   const int ntl = sh->NT2 ? sh->NT2 : sh->NT1;
   sh->raw_member_floats = sh->P * sh->H1 + sh->H1 + (sh->H2 ? sh->H1 * sh->H2 + sh->H2 + sh->H2 : sh->H1) + 1;
-  if (sh->net == NET_F32_MFMA) {
+  // Parameters whose stride is a multiple of the tile size (32) have one value per tile
+  // of 32 consecutive configurations that starts at a multiple of 32; they are the leading
+  // ones.  The fp32 matrix network can take their layer-1 share out of the matrix
+  // instructions (net_f32h.h) when at most 8 parameters remain and at least 2 are taken out.
+  sh->hoist = 0;
+  if (sh->net == NET_F32_MFMA && allow_hoist) {
+    int p0 = 0;
+    while (p0 < sh->P && sp->strides[p0] % 32 == 0) ++p0;
+    const int n_low = sh->P - p0;
+    if (p0 >= 2 && n_low >= 1 && n_low <= 8) {
+      sh->hoist = 1;
+      sh->p0 = p0;
+      sh->n_high4 = round_up(p0, 4);
+    }
+  }
+  if (sh->net == NET_F32_MFMA && sh->hoist) {
+    sh->NPL = 1;
+    sh->KS = (sh->P - sh->p0 + 1) / 2;         // steps of 2 low inputs (no bias column)
+    sh->o_w1 = 0;
+    sh->o_w2 = sh->NT1 * round_up(sh->KS, 4) * 64;
+    sh->o_b1 = sh->o_w2 + sh->NT2 * sh->NT1 * 16 * 64;
+    sh->o_b2 = sh->o_b1;
+    sh->o_wo = sh->o_b2 + sh->NT2 * 32;
+    sh->o_wh = sh->o_wo + ntl * 32;
+    sh->member_words = sh->o_wh + (sh->n_high4 + 1) * sh->NT1 * 32;
+  } else if (sh->net == NET_F32_MFMA) {
     sh->NPL = 1;
     sh->KS = round_up(sh->P + 1, 4) / 2;       // steps of 2 inputs (bias column included), even
     sh->o_w1 = 0;
@@ -322,7 +349,7 @@ static int make_shape(const tuner_space* sp, const tuner_model* m, Shape* sh) {
 }
 
 static const Variant* find_variant(const Shape& sh) {
-  if (sh.net == NET_F32_MFMA) return find_variant_f32(sh.KS, sh.NT1, sh.NT2);
+  if (sh.net == NET_F32_MFMA) return sh.hoist ? find_variant_f32h(sh.KS, sh.NT1, sh.NT2) : find_variant_f32(sh.KS, sh.NT1, sh.NT2);
   if (sh.net == NET_BF16 || sh.net == NET_F16X2) return find_variant_lp(sh.net, sh.KS, sh.NT1, sh.NT2);
   if (sh.net == NET_F32_VALU) return find_variant_valu(sh.KS, sh.NT1, sh.NT2);
   return nullptr;
@@ -339,6 +366,7 @@ static const Variant* find_variant(const Shape& sh) {
 // ---------------------------------------------------------------------------
 struct ClassifyParams {
   uint64_t begin, count;
+  uint32_t head;              // positions of the range before the caller's first configuration
   uint32_t n_chunks, iter;
   float* pred;                // predict_all: wholly invalid chunks get their +inf (and mask 0) here
   uint8_t* mask;
@@ -384,6 +412,7 @@ __global__ void __launch_bounds__(256) classify_kernel(const DevSpace sp, const 
         const uint64_t t0 = (uint64_t)(base + j) * cp.iter;
         const uint64_t left = cp.count - t0 < (uint64_t)cp.iter ? cp.count - t0 : (uint64_t)cp.iter;
         for (uint64_t x = threadIdx.x; x < left; x += blockDim.x) {
+          if (t0 + x < cp.head) continue;
           cp.pred[t0 + x] = __builtin_inff();
           if (cp.mask) cp.mask[t0 + x] = 0;
         }
@@ -447,7 +476,7 @@ static int run_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin
                      float* pred, uint8_t* mask, void* ws, size_t ws_bytes, hipStream_t stream,
                      const uint32_t* index_list = nullptr) {
   Shape sh{};
-  int rc = make_shape(sp, m, &sh);
+  int rc = make_shape(sp, m, &sh, !index_list);
   if (rc) return rc;
   const Variant* var = find_variant(sh);
   if (!var) return set_error(TUNER_ETOOLARGE, "no kernel variant for this model shape");
@@ -455,6 +484,19 @@ static int run_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin
     if (count > (1ull << 32)) return set_error(TUNER_ETOOLARGE, "more than 2^32 list entries");
   } else if (begin > sp->n_configs || count > sp->n_configs - begin) {
     return set_error(TUNER_EINVAL, "range outside the space");
+  }
+  // The hoisting network needs tiles that start at multiples of 32 in the space: the swept
+  // range is extended downwards to one, and the `head` positions before the caller's range
+  // are masked (outputs are addressed through pointers shifted by the same amount).  A
+  // configuration is then evaluated in the same place of the same tile whatever the range,
+  // so results do not depend on how a sweep is cut into calls.
+  uint32_t head = 0;
+  if (sh.hoist) {
+    head = (uint32_t)(begin % 32);
+    begin -= head;
+    count += head;
+    if (pred) pred -= head;
+    if (mask) mask -= head;
   }
   const Layout L = make_layout(sh, k, sp->n_configs, var);
   if (!ws || ws_bytes < L.total) return set_error(TUNER_EWORKSPACE, "workspace missing or too small");
@@ -514,7 +556,9 @@ static int run_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin
   uint32_t groups = std::min<uint32_t>(n_units, max_groups);
 
   if (groups > 0) {
-    const int budget = di.max_lds - kSpaceBytes - 64;   // 64 B of static LDS
+    // the hoisting network keeps, per wave, the high features of its tiles and one z vector
+    const int hoist_bytes = sh.hoist ? var->waves * (var->R * 32 + std::max(64, sh.NT1 * 32)) * 4 : 0;
+    const int budget = di.max_lds - kSpaceBytes - 64 - hoist_bytes;   // 64 B of static LDS
     const int member_bytes = sh.member_words * 4;
     int mps = budget / member_bytes;
     if (mps < 1) return set_error(TUNER_ETOOLARGE, "one packed member does not fit in LDS");
@@ -529,6 +573,7 @@ static int run_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin
     SweepParams sw{};
     sw.begin = begin;
     sw.count = count;
+    sw.head = head;
     sw.n_chunks = n_chunks;
     sw.n_units = n_units;
     sw.super = (int32_t)super;
@@ -537,7 +582,7 @@ static int run_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin
     sw.members_per_stage = mps;
     sw.n_stages = (sh.E + mps - 1) / mps;
     sw.member_words = sh.member_words;
-    sw.off = NetOffsets{sh.o_w1, sh.o_w2, sh.o_b1, sh.o_b2, sh.o_wo, sh.H1, sh.H2};
+    sw.off = NetOffsets{sh.o_w1, sh.o_w2, sh.o_b1, sh.o_b2, sh.o_wo, sh.H1, sh.H2, sh.o_wh, sh.p0, sh.n_high4};
     sw.mode = mode;
     sw.inv_members = (float)(1.0 / (double)sh.E);
     sw.k = k;
@@ -559,6 +604,7 @@ static int run_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin
       ClassifyParams cp{};
       cp.begin = begin;
       cp.count = count;
+      cp.head = head;
       cp.n_chunks = n_chunks;
       cp.iter = (uint32_t)iter;
       cp.pred = mode == MODE_ALL ? pred : nullptr;
@@ -598,6 +644,8 @@ static int run_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin
         lds = (size_t)kSpaceBytes + weights_bytes + (size_t)entries * 8;
       }
     }
+    sw.hoist_offset = (uint32_t)((lds + 15) / 16 * 16);
+    lds = (size_t)sw.hoist_offset + (size_t)hoist_bytes;
     TUNER_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(var->fn),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
@@ -680,10 +728,24 @@ extern "C" {
 size_t tuner_workspace_bytes(const tuner_space* space, const tuner_model* model, int32_t k) {
   if (!space || !model) { set_error(TUNER_EINVAL, "null argument"); return 0; }
   if (k < 0 || k > TUNER_MAX_K) { set_error(TUNER_ETOOLARGE, "k out of range"); return 0; }
+  size_t need = 0;
+  for (int hoist = 0; hoist < 2; ++hoist) {     // a call may use either layout of the packed weights
+    tuner::Shape sh{};
+    if (tuner::make_shape(space, model, &sh, hoist != 0)) return 0;
+    const tuner::Variant* var = tuner::find_variant(sh);
+    if (!var) { set_error(TUNER_ETOOLARGE, "no kernel variant for this model shape"); return 0; }
+    need = std::max(need, tuner::make_layout(sh, k, space->n_configs, var).total);
+  }
+  return need;
+}
+
+int tuner_hoisted_parameters(const tuner_space* space, const tuner_model* model, int32_t* n_hoisted) {
+  if (!space || !model || !n_hoisted) return set_error(TUNER_EINVAL, "null argument");
   tuner::Shape sh{};
-  if (tuner::make_shape(space, model, &sh)) return 0;
-  if (!tuner::find_variant(sh)) { set_error(TUNER_ETOOLARGE, "no kernel variant for this model shape"); return 0; }
-  return tuner::make_layout(sh, k, space->n_configs, tuner::find_variant(sh)).total;
+  const int rc = tuner::make_shape(space, model, &sh, true);
+  if (rc) return rc;
+  *n_hoisted = sh.hoist ? sh.p0 : 0;
+  return TUNER_OK;
 }
 
 int tuner_profile_enable(int32_t on) {

@@ -107,13 +107,17 @@ def test_predict_indices_matches_oracle(maker, n):
     assert np.array_equal(mask.cpu().numpy(), ov)
     worst, rel = parity.check_predictions(pred.cpu().numpy(), oy, ov)
     say(f"  worst {worst:.3f} x tol, pure-relative worst {rel:.2e}")
-    # the same configurations through the range entry point give the same bits
+    # the same configurations through the range entry point: same values up to the order of
+    # the fp32 additions (a range sweep may take the layer-1 share of the parameters that are
+    # constant over a tile out of the matrix instructions; a list cannot)
     lo = int(idx[-1])
     cnt = int(min(64, sp.n_configs - lo))
-    a, _ = sw.predict_all(lo, cnt)
-    b, _ = sw.predict_indices(dev_u32(np.arange(lo, lo + cnt, dtype=np.uint64)))
+    a, ma = sw.predict_all(lo, cnt)
+    b, mb = sw.predict_indices(dev_u32(np.arange(lo, lo + cnt, dtype=np.uint64)))
     torch.cuda.synchronize()
-    assert torch.equal(a, b)
+    assert torch.equal(ma, mb)
+    va, vb = a[ma.bool()], b[mb.bool()]
+    assert bool(torch.all(torch.abs(va - vb) <= 2e-6 * torch.clamp(torch.abs(va), min=1.0)))
 
 
 # --------------------------------------------------------------- training ----

@@ -187,6 +187,23 @@ def test_predict_argument_errors_before_any_gpu_work():
     assert L.tuner_decode_range(None, 0, 1, None, None, None, None) == T.TUNER_EINVAL
 
 
+def test_which_parameters_are_constant_over_a_tile():
+    """The fp32 matrix network takes the layer-1 share of the leading parameters whose stride
+    is a multiple of 32 out of the matrix instructions when at most 8 parameters remain."""
+    def hoisted(w, **kw):
+        h = make_space(w.space)
+        return T.tuner_hoisted_parameters(h, T.ModelHandle(w.model.n_members, w.model.widths, _FakeWeights(), **kw))
+    assert hoisted(wl.large()) == 9            # 2^27: the last five parameters span 32 configurations
+    assert hoisted(wl.streamed()) == 15        # 2^32: 20 parameters, the last five are boolean
+    assert hoisted(wl.wide()) == 9
+    assert hoisted(wl.conv_shaped()) == 4      # strides ..., 96, 48, 24, 12, 6, 3, 1
+    assert hoisted(wl.tiny()) == 0             # 256 configurations: only one stride is a multiple of 32
+    assert hoisted(wl.paper_stereo()) == 5     # strides 294912, 36864, 4608, 576, 288 | 144, 72, 36, 9, 3, 1
+    assert hoisted(wl.large(), algo=T.TUNER_ALGO_SPLIT16) == 0
+    assert hoisted(wl.large(), algo=T.TUNER_ALGO_VALU) == 0
+    assert hoisted(wl.large(), precision=T.TUNER_BF16_MFMA) == 0
+
+
 def test_tuner_stage_argument_errors_before_any_gpu_work():
     """Sampler, training, list evaluation, metric and second-stage entry points reject bad
     calls on the host (no HIP call is reached)."""
