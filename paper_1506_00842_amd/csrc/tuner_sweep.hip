@@ -552,6 +552,19 @@ static int run_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin
   // queue unit: up to kMaxSuper chunks, while every workgroup still gets >= 8 units
   uint32_t super = 1;
   while (super < (uint32_t)kMaxSuper && n_chunks64 / (2 * super) >= 8ull * max_groups) super *= 2;
+  // a resident ensemble keeps its candidate pool (2 k keys + one queue unit) in LDS too if
+  // it fits; a smaller unit is worth that
+  if (mode == MODE_TOPK && k > 0) {
+    const size_t hoist_b = sh.hoist ? (size_t)var->waves * (var->R * 32 + std::max(64, sh.NT1 * 32)) * 4 : 0;
+    const size_t free_b = (size_t)di.max_lds - kSpaceBytes - 64 - hoist_b;
+    const size_t weights_b = ((size_t)sh.E * sh.member_words * 4 + 15) / 16 * 16;
+    if (weights_b < free_b) {
+      const uint32_t kp2 = 2u * host_next_pow2((uint32_t)k);
+      while (super > 1 && (size_t)host_next_pow2(kp2 + super * (uint32_t)iter) * 8 > free_b - weights_b &&
+             (size_t)host_next_pow2(kp2 + (super / 2) * (uint32_t)iter) * 8 <= free_b - weights_b)
+        super /= 2;
+    }
+  }
   const uint32_t n_units = (uint32_t)((n_chunks64 + super - 1) / super);
   uint32_t groups = std::min<uint32_t>(n_units, max_groups);
 
