@@ -17,8 +17,7 @@
 // Packed member (fp32 words), hidden-layer weights and biases times -log2(e):
 //   W1A [NT1][ceil(KSL/4)][64 lanes][4]  lane (n, h), step s = 4 sg + j: W1[32 t + n][p0 + 2 s + h]
 //   W2A, b2A, woA                        as in net_f32.h
-//   WH  [n_high4 + 1][NT1 * 32]          row p < p0: W1[u][p]; rows p0 .. n_high4-1: 0;
-//                                        row n_high4: b1[u]      (n_high4 = p0 rounded up to 4)
+//   WH  [p0 + 1][NT1 * 32]               row p < p0: W1[u][p]; row p0: b1[u]
 #pragma once
 #include "net_f32.h"
 
@@ -68,12 +67,13 @@ struct F32HNet {
     // z_high, one unit per lane (kUnits / 64 units per lane for the wide nets)
     {
       const float* wh = w + o.wh;
-      const int n4 = o.n_high4;
+      const int p0 = o.p0;
       constexpr int UPL = kUnits > 64 ? kUnits / 64 : 1;
       float z[UPL];
 #pragma unroll
-      for (int q = 0; q < UPL; ++q) z[q] = wh[n4 * kUnits + ((lane + 64 * q) % kUnits)];
-      for (int p = 0; p < n4; p += 4) {
+      for (int q = 0; q < UPL; ++q) z[q] = wh[p0 * kUnits + ((lane + 64 * q) % kUnits)];
+      int p = 0;
+      for (; p + 4 <= p0; p += 4) {
         const float4 x = *reinterpret_cast<const float4*>(xs + p);   // same address in every lane
 #pragma unroll
         for (int q = 0; q < UPL; ++q) {
@@ -83,6 +83,11 @@ struct F32HNet {
           z[q] = fmaf(wh[(p + 2) * kUnits + u], x.z, z[q]);
           z[q] = fmaf(wh[(p + 3) * kUnits + u], x.w, z[q]);
         }
+      }
+      for (; p < p0; ++p) {
+        const float x = xs[p];
+#pragma unroll
+        for (int q = 0; q < UPL; ++q) z[q] = fmaf(wh[p * kUnits + ((lane + 64 * q) % kUnits)], x, z[q]);
       }
 #pragma unroll
       for (int q = 0; q < UPL; ++q) zs[lane + 64 * q] = z[q];
@@ -138,7 +143,7 @@ __device__ inline float pack_word_f32h(const Shape& sh, const float* raw, int q)
     const int row = q / units, u = q - row * units;
     if (u < sh.H1) {
       if (row < sh.p0) v = raw[r_w1 + u * sh.P + row] * kNegLog2e;
-      else if (row == sh.n_high4) v = raw[r_b1 + u] * kNegLog2e;
+      else if (row == sh.p0) v = raw[r_b1 + u] * kNegLog2e;
     }
   }
   return v;

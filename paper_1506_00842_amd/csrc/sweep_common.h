@@ -45,11 +45,10 @@ struct Shape {
   // fp32 matrix network with the high parameters' layer-1 share computed once per tile
   int hoist;                  // 0 / 1
   int p0;                     // parameters 0 .. p0-1 are constant over a tile of 32 configurations
-  int n_high4;                // p0 rounded up to a multiple of 4
-  int o_wh;                   // their weights, [n_high4 + 1][NT1 * 32]
+  int o_wh;                   // their weights and the bias, [p0 + 1][NT1 * 32]
 };
 
-struct NetOffsets { int w1, w2, b1, b2, wo, h1, h2, wh, p0, n_high4; };   // word offsets; real hidden widths; hoisting
+struct NetOffsets { int w1, w2, b1, b2, wo, h1, h2, wh, p0; };   // word offsets; real hidden widths; hoisting
 
 struct SweepParams {
   uint64_t begin, count;

@@ -303,7 +303,6 @@ static int make_shape(const tuner_space* sp, const tuner_model* m, Shape* sh, bo
     if (p0 >= 2 && n_low >= 1 && n_low <= 8) {
       sh->hoist = 1;
       sh->p0 = p0;
-      sh->n_high4 = round_up(p0, 4);
     }
   }
   if (sh->net == NET_F32_MFMA && sh->hoist) {
@@ -315,7 +314,7 @@ static int make_shape(const tuner_space* sp, const tuner_model* m, Shape* sh, bo
     sh->o_b2 = sh->o_b1;
     sh->o_wo = sh->o_b2 + sh->NT2 * 32;
     sh->o_wh = sh->o_wo + ntl * 32;
-    sh->member_words = sh->o_wh + (sh->n_high4 + 1) * sh->NT1 * 32;
+    sh->member_words = sh->o_wh + round_up((sh->p0 + 1) * sh->NT1 * 32, 4);
   } else if (sh->net == NET_F32_MFMA) {
     sh->NPL = 1;
     sh->KS = round_up(sh->P + 1, 4) / 2;       // steps of 2 inputs (bias column included), even
@@ -595,7 +594,7 @@ static int run_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin
     sw.members_per_stage = mps;
     sw.n_stages = (sh.E + mps - 1) / mps;
     sw.member_words = sh.member_words;
-    sw.off = NetOffsets{sh.o_w1, sh.o_w2, sh.o_b1, sh.o_b2, sh.o_wo, sh.H1, sh.H2, sh.o_wh, sh.p0, sh.n_high4};
+    sw.off = NetOffsets{sh.o_w1, sh.o_w2, sh.o_b1, sh.o_b2, sh.o_wo, sh.H1, sh.H2, sh.o_wh, sh.p0};
     sw.mode = mode;
     sw.inv_members = (float)(1.0 / (double)sh.E);
     sw.k = k;
