@@ -268,6 +268,11 @@ def main():
     # computed once per tile, i.e. 31/32 of those multiply-adds are never executed
     n_hoisted = T.tuner_hoisted_parameters(sw.space, sw.model)
     executed_flop_per_cfg = flop_per_cfg - 2.0 * m.n_members * m.widths[1] * n_hoisted * 31.0 / 32.0
+    # layer-1 share of the remaining parameters read from a per-member table: no multiply-adds
+    # per configuration but the one matrix step (2 inputs) that adds the tile's vector to the table
+    n_tabulated = T.tuner_tabulated_parameters(sw.space, sw.model) if args.net == "f32-mfma" else 0
+    if n_tabulated:
+        executed_flop_per_cfg -= 2.0 * m.n_members * m.widths[1] * (n_tabulated - 2)
     launches_per_step = n_launch / args.steps
     kernel_ms = sweep_ms / max(n_launch, 1)
     roof = None
@@ -282,7 +287,8 @@ def main():
                 "kernel": "sweep_kernel (fp32 MFMA 32x32x2)", "kernel_ms": kernel_ms,
                 "launches_per_step": launches_per_step,
                 "flop_per_config": flop_per_cfg, "evaluated_configs_per_launch": n_valid / launches_per_step,
-                "hoisted_parameters": n_hoisted, "executed_flop_per_config": executed_flop_per_cfg,
+                "hoisted_parameters": n_hoisted, "tabulated_parameters": n_tabulated,
+                "executed_flop_per_config": executed_flop_per_cfg,
                 "frac_executed": achieved * executed_flop_per_cfg / flop_per_cfg / PEAK_FP32_MATRIX_TFLOPS,
                 "sigmoids_per_config": m.sigmoids_per_config}
     out = {

@@ -155,6 +155,18 @@ size_t tuner_workspace_bytes(const tuner_space* space, const tuner_model* model,
 int tuner_hoisted_parameters(const tuner_space* space, const tuner_model* model, int32_t* n_hoisted);
 
 /*
+ * Companion of tuner_hoisted_parameters (host only).  When the remaining parameters
+ * (stride < 32) span exactly 32 configurations, configuration c of every tile has the
+ * same values for them (Section 5.1: Cartesian product, last parameter fastest), and
+ * their share of the layer-1 pre-activations is a [units][32] table per member, built
+ * when the weights are packed, instead of matrix work per configuration.  The library
+ * does this when the larger packed members still fit the 160 KB of LDS either all at
+ * once or as two stage buffers.  *n_tabulated receives the number of parameters served
+ * from the table (0: none).
+ */
+int tuner_tabulated_parameters(const tuner_space* space, const tuner_model* model, int32_t* n_tabulated);
+
+/*
  * Sweep of indices [index_begin, index_begin + index_count) and selection of
  * the k valid configurations with the smallest predictions, ordered by
  * (prediction, then index), ascending (Section 5.3).

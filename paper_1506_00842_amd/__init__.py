@@ -28,7 +28,7 @@ EXPORTS = [
     "tuner_space_create", "tuner_space_destroy", "tuner_space_size", "tuner_space_decode",
     "tuner_space_encode", "tuner_space_decode_device_arith", "tuner_workspace_bytes",
     "tuner_predict_topk", "tuner_predict_all", "tuner_decode_range", "tuner_last_error",
-    "tuner_version", "tuner_profile_enable", "tuner_profile_read", "tuner_profile_read_train", "tuner_hoisted_parameters",
+    "tuner_version", "tuner_profile_enable", "tuner_profile_read", "tuner_profile_read_train", "tuner_hoisted_parameters", "tuner_tabulated_parameters",
     "tuner_predict_indices", "tuner_sample_workspace_bytes", "tuner_sample_valid",
     "tuner_train_workspace_bytes", "tuner_train_ensemble", "tuner_mean_relative_error",
     "tuner_best_of",
@@ -77,6 +77,7 @@ def load_library():
                                      C.c_void_p, C.c_void_p, C.POINTER(C.c_void_p)]
     L.tuner_space_destroy.argtypes = [C.c_void_p]
     L.tuner_hoisted_parameters.argtypes = [C.c_void_p, C.POINTER(_Model), C.POINTER(C.c_int32)]
+    L.tuner_tabulated_parameters.argtypes = [C.c_void_p, C.POINTER(_Model), C.POINTER(C.c_int32)]
     L.tuner_space_size.argtypes = [C.c_void_p, C.POINTER(C.c_uint64)]
     L.tuner_space_decode.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p,
                                      C.POINTER(C.c_int32)]
@@ -121,6 +122,12 @@ def tuner_last_error() -> str:
 def tuner_hoisted_parameters(space, model) -> int:
     n = C.c_int32(0)
     _check(load_library().tuner_hoisted_parameters(space.ptr, C.byref(model.c), C.byref(n)))
+    return int(n.value)
+
+
+def tuner_tabulated_parameters(space, model) -> int:
+    n = C.c_int32(0)
+    _check(load_library().tuner_tabulated_parameters(space.ptr, C.byref(model.c), C.byref(n)))
     return int(n.value)
 
 

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libtuner_hip.so")
-SOURCES = ["tuner_space.hip", "tuner_sweep.hip", "sweep_f32.hip", "sweep_f32h.hip", "sweep_lp.hip", "sweep_valu.hip", "tuner_train.hip"]
+SOURCES = ["tuner_space.hip", "tuner_sweep.hip", "sweep_f32.hip", "sweep_f32h.hip", "sweep_f32t.hip", "sweep_lp.hip", "sweep_valu.hip", "tuner_train.hip"]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",
          # packed fp32 VALU instructions are kept out of the generated code
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -12,6 +12,7 @@ constexpr int kMergeThreads = 1024;
 constexpr int kMaxGroups = 256;           // persistent workgroups (MI355X: 256 CUs)
 constexpr int kMaxIter = 1024;            // most configurations per chunk (waves * R * tile) over all variants
 constexpr int kMaxSuper = 4;              // most chunks per queue unit
+constexpr int kLdsBytesPerWorkgroup = 160 * 1024;   // gfx950; host-only queries plan with it
 constexpr unsigned long long kKeyMax = ~0ull;
 constexpr int kSpaceBytes = (sizeof(DevSpace) + 255) / 256 * 256;
 constexpr float kNegLog2e = -1.44269504088896340736f;
@@ -43,9 +44,9 @@ struct Shape {
   int member_words;           // multiple of 4
   int raw_member_floats;
   // fp32 matrix network with the high parameters' layer-1 share computed once per tile
-  int hoist;                  // 0 / 1
+  int hoist;                  // 0: no; 1: high share once per tile (net_f32h.h); 2: also the low share from a table (net_f32t.h)
   int p0;                     // parameters 0 .. p0-1 are constant over a tile of 32 configurations
-  int o_wh;                   // their weights and the bias, [p0 + 1][NT1 * 32]
+  int o_wh;                   // their weights and the bias (layout of the network's header)
 };
 
 struct NetOffsets { int w1, w2, b1, b2, wo, h1, h2, wh, p0; };   // word offsets; real hidden widths; hoisting
@@ -85,6 +86,7 @@ struct Variant { int net, KS, NT1, NT2, R, waves, tile; SweepFn fn; };
 // Lookups implemented next to the instantiations (one translation unit per family).
 const Variant* find_variant_f32(int KS, int NT1, int NT2);
 const Variant* find_variant_f32h(int KSL, int NT1, int NT2);
+const Variant* find_variant_f32t(int NT1, int NT2);
 const Variant* find_variant_lp(int net, int KS, int NT1, int NT2);
 const Variant* find_variant_valu(int KS, int NT1, int NT2);
 

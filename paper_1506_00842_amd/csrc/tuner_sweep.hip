@@ -25,6 +25,7 @@
 
 #include "net_f32.h"
 #include "net_f32h.h"
+#include "net_f32t.h"
 #include "net_lp.h"
 #include "net_valu.h"
 #include "sweep_common.h"
@@ -64,6 +65,7 @@ __global__ void __launch_bounds__(256) prep_kernel(const DevSpace sp, const Prep
     if (sh.net == NET_BF16) word = pack_word_lp<__bf16>(sh, raw, q);
     else if (sh.net == NET_F16X2) word = pack_word_lp<_Float16>(sh, raw, q);
     else if (sh.net == NET_F32_VALU) word = __float_as_uint(pack_word_valu(sh, raw, q));
+    else if (sh.hoist == 2) word = __float_as_uint(pack_word_f32t(sh, raw, q, sp));
     else if (sh.hoist) word = __float_as_uint(pack_word_f32h(sh, raw, q));
     else word = __float_as_uint(pack_word_f32(sh, raw, q));
     pp.packed[x] = word;
@@ -260,7 +262,9 @@ finalize_kernel(const unsigned long long* list, int32_t k, float* values, uint32
 // ---------------------------------------------------------------------------
 static int round_up(int v, int m) { return (v + m - 1) / m * m; }
 
-static int make_shape(const tuner_space* sp, const tuner_model* m, Shape* sh, bool allow_hoist = false) {
+// allow_hoist: 0 = plain layer 1; 1 = the tile-constant parameters' share once per tile;
+// 2 = also the remaining parameters' share from a table, where the space allows it.
+static int make_shape(const tuner_space* sp, const tuner_model* m, Shape* sh, int allow_hoist = 0) {
   if (!m->widths || !m->weights_dev) return set_error(TUNER_EINVAL, "null model arrays");
   if (m->n_members < 1) return set_error(TUNER_EINVAL, "n_members < 1");
   if (m->n_layers != 2 && m->n_layers != 3) return set_error(TUNER_EINVAL, "n_layers must be 2 or 3");
@@ -303,9 +307,22 @@ static int make_shape(const tuner_space* sp, const tuner_model* m, Shape* sh, bo
     if (p0 >= 2 && n_low >= 1 && n_low <= 8) {
       sh->hoist = 1;
       sh->p0 = p0;
+      // the remaining parameters span exactly one tile: their values repeat from tile to
+      // tile, and their layer-1 share is a per-member table (net_f32t.h)
+      if (allow_hoist >= 2 && sp->strides[p0 - 1] == 32) sh->hoist = 2;
     }
   }
-  if (sh->net == NET_F32_MFMA && sh->hoist) {
+  if (sh->net == NET_F32_MFMA && sh->hoist == 2) {
+    sh->NPL = 1;
+    sh->KS = 0;
+    sh->o_w1 = 0;                                        // the table
+    sh->o_w2 = sh->NT1 * 16 * 64;
+    sh->o_b1 = sh->o_w2 + sh->NT2 * sh->NT1 * 16 * 64;
+    sh->o_b2 = sh->o_b1;
+    sh->o_wo = sh->o_b2 + sh->NT2 * 32;
+    sh->o_wh = sh->o_wo + ntl * 32;
+    sh->member_words = sh->o_wh + sh->NT1 * f32t_term_groups(sh->p0) * 256;
+  } else if (sh->net == NET_F32_MFMA && sh->hoist) {
     sh->NPL = 1;
     sh->KS = (sh->P - sh->p0 + 1) / 2;         // steps of 2 low inputs (no bias column)
     sh->o_w1 = 0;
@@ -348,7 +365,10 @@ static int make_shape(const tuner_space* sp, const tuner_model* m, Shape* sh, bo
 }
 
 static const Variant* find_variant(const Shape& sh) {
-  if (sh.net == NET_F32_MFMA) return sh.hoist ? find_variant_f32h(sh.KS, sh.NT1, sh.NT2) : find_variant_f32(sh.KS, sh.NT1, sh.NT2);
+  if (sh.net == NET_F32_MFMA) {
+    if (sh.hoist == 2) return find_variant_f32t(sh.NT1, sh.NT2);
+    return sh.hoist ? find_variant_f32h(sh.KS, sh.NT1, sh.NT2) : find_variant_f32(sh.KS, sh.NT1, sh.NT2);
+  }
   if (sh.net == NET_BF16 || sh.net == NET_F16X2) return find_variant_lp(sh.net, sh.KS, sh.NT1, sh.NT2);
   if (sh.net == NET_F32_VALU) return find_variant_valu(sh.KS, sh.NT1, sh.NT2);
   return nullptr;
@@ -470,15 +490,55 @@ static int device_info(DeviceInfo* out) {
   return TUNER_OK;
 }
 
+// LDS bytes of the hoisting networks' per-wave scratch: the high features of a wave's
+// tiles, and for net_f32h.h one z_high vector.
+static int hoist_scratch_bytes(const Shape& sh, const Variant* var) {
+  if (!sh.hoist) return 0;
+  const int z = sh.hoist == 1 ? std::max(64, sh.NT1 * 32) : 0;
+  return var->waves * (var->R * 32 + z) * 4;
+}
+
+// How the ensemble goes through LDS: all members resident, or stages of `mps` members.
+// Members that do not all fit are streamed through two half-size buffers if a member fits
+// one half: the next stage loads while the current one is evaluated.
+struct StagePlan { int budget = 0, mps = 0; bool double_buffer = false; };
+
+static StagePlan plan_stages(const Shape& sh, const Variant* var, int max_lds) {
+  StagePlan pl;
+  pl.budget = max_lds - kSpaceBytes - 64 - hoist_scratch_bytes(sh, var);   // 64 B of static LDS
+  const int member_bytes = sh.member_words * 4;
+  pl.mps = pl.budget > 0 ? std::min(pl.budget / member_bytes, sh.E) : 0;
+  if (pl.mps >= 1 && pl.mps < sh.E && (pl.budget / 2) / member_bytes >= 1) {
+    pl.mps = (pl.budget / 2) / member_bytes;
+    pl.double_buffer = true;
+  }
+  return pl;
+}
+
+// Shape and kernel variant of a sweep.  Range sweeps (hoist_ok) take the layer-1 shortcuts
+// the space allows; the table of the low parameters' share makes a member larger, so it is
+// used only while the ensemble stays resident in LDS or keeps its two stage buffers.
+static int choose_shape(const tuner_space* sp, const tuner_model* m, bool hoist_ok, int max_lds, Shape* sh,
+                        const Variant** var) {
+  for (int level = hoist_ok ? 2 : 0; ; --level) {
+    const int rc = make_shape(sp, m, sh, level);
+    if (rc) return rc;
+    *var = find_variant(*sh);
+    if (!*var) return set_error(TUNER_ETOOLARGE, "no kernel variant for this model shape");
+    if (sh->hoist < 2) return TUNER_OK;
+    const StagePlan pl = plan_stages(*sh, *var, max_lds);
+    if (pl.mps >= sh->E || pl.double_buffer) return TUNER_OK;
+  }
+}
+
 static int run_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin, uint64_t count,
                      int mode, int k, int merge, float* values, uint32_t* indices, int32_t* n_found,
                      float* pred, uint8_t* mask, void* ws, size_t ws_bytes, hipStream_t stream,
                      const uint32_t* index_list = nullptr) {
   Shape sh{};
-  int rc = make_shape(sp, m, &sh, !index_list);
+  const Variant* var = nullptr;
+  int rc = choose_shape(sp, m, !index_list, kLdsBytesPerWorkgroup, &sh, &var);
   if (rc) return rc;
-  const Variant* var = find_variant(sh);
-  if (!var) return set_error(TUNER_ETOOLARGE, "no kernel variant for this model shape");
   if (index_list) {
     if (count > (1ull << 32)) return set_error(TUNER_ETOOLARGE, "more than 2^32 list entries");
   } else if (begin > sp->n_configs || count > sp->n_configs - begin) {
@@ -554,7 +614,7 @@ static int run_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin
   // a resident ensemble keeps its candidate pool (2 k keys + one queue unit) in LDS too if
   // it fits; a smaller unit is worth that
   if (mode == MODE_TOPK && k > 0) {
-    const size_t hoist_b = sh.hoist ? (size_t)var->waves * (var->R * 32 + std::max(64, sh.NT1 * 32)) * 4 : 0;
+    const size_t hoist_b = (size_t)hoist_scratch_bytes(sh, var);
     const size_t free_b = (size_t)di.max_lds - kSpaceBytes - 64 - hoist_b;
     const size_t weights_b = ((size_t)sh.E * sh.member_words * 4 + 15) / 16 * 16;
     if (weights_b < free_b) {
@@ -568,20 +628,11 @@ static int run_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin
   uint32_t groups = std::min<uint32_t>(n_units, max_groups);
 
   if (groups > 0) {
-    // the hoisting network keeps, per wave, the high features of its tiles and one z vector
-    const int hoist_bytes = sh.hoist ? var->waves * (var->R * 32 + std::max(64, sh.NT1 * 32)) * 4 : 0;
-    const int budget = di.max_lds - kSpaceBytes - 64 - hoist_bytes;   // 64 B of static LDS
-    const int member_bytes = sh.member_words * 4;
-    int mps = budget / member_bytes;
-    if (mps < 1) return set_error(TUNER_ETOOLARGE, "one packed member does not fit in LDS");
-    mps = std::min(mps, sh.E);
-    // members that do not all fit are streamed through two half-size buffers if a
-    // member fits one half: the next stage loads while the current one is evaluated
-    bool double_buffer = false;
-    if (mps < sh.E && (budget / 2) / member_bytes >= 1) {
-      mps = (budget / 2) / member_bytes;
-      double_buffer = true;
-    }
+    const int hoist_bytes = hoist_scratch_bytes(sh, var);
+    const StagePlan pl = plan_stages(sh, var, di.max_lds);
+    if (pl.mps < 1) return set_error(TUNER_ETOOLARGE, "one packed member does not fit in LDS");
+    const int budget = pl.budget, mps = pl.mps, member_bytes = sh.member_words * 4;
+    const bool double_buffer = pl.double_buffer;
     SweepParams sw{};
     sw.begin = begin;
     sw.count = count;
@@ -741,9 +792,9 @@ size_t tuner_workspace_bytes(const tuner_space* space, const tuner_model* model,
   if (!space || !model) { set_error(TUNER_EINVAL, "null argument"); return 0; }
   if (k < 0 || k > TUNER_MAX_K) { set_error(TUNER_ETOOLARGE, "k out of range"); return 0; }
   size_t need = 0;
-  for (int hoist = 0; hoist < 2; ++hoist) {     // a call may use either layout of the packed weights
+  for (int level = 0; level <= 2; ++level) {     // a call may use any layout of the packed weights
     tuner::Shape sh{};
-    if (tuner::make_shape(space, model, &sh, hoist != 0)) return 0;
+    if (tuner::make_shape(space, model, &sh, level)) return 0;
     const tuner::Variant* var = tuner::find_variant(sh);
     if (!var) { set_error(TUNER_ETOOLARGE, "no kernel variant for this model shape"); return 0; }
     need = std::max(need, tuner::make_layout(sh, k, space->n_configs, var).total);
@@ -754,9 +805,19 @@ size_t tuner_workspace_bytes(const tuner_space* space, const tuner_model* model,
 int tuner_hoisted_parameters(const tuner_space* space, const tuner_model* model, int32_t* n_hoisted) {
   if (!space || !model || !n_hoisted) return set_error(TUNER_EINVAL, "null argument");
   tuner::Shape sh{};
-  const int rc = tuner::make_shape(space, model, &sh, true);
+  const int rc = tuner::make_shape(space, model, &sh, 1);
   if (rc) return rc;
   *n_hoisted = sh.hoist ? sh.p0 : 0;
+  return TUNER_OK;
+}
+
+int tuner_tabulated_parameters(const tuner_space* space, const tuner_model* model, int32_t* n_tabulated) {
+  if (!space || !model || !n_tabulated) return set_error(TUNER_EINVAL, "null argument");
+  tuner::Shape sh{};
+  const tuner::Variant* var = nullptr;
+  const int rc = tuner::choose_shape(space, model, true, tuner::kLdsBytesPerWorkgroup, &sh, &var);
+  if (rc) return rc;
+  *n_tabulated = sh.hoist == 2 ? sh.P - sh.p0 : 0;
   return TUNER_OK;
 }
 

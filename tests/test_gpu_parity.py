@@ -97,6 +97,22 @@ def test_predict_all_model_shapes(P, hidden, E):
     _check_range(wp, n - count, count)
 
 
+# How many configurations the fastest parameters span decides how the fp32 matrix network
+# evaluates layer 1: (4, 3, 3) = 36 -> high share once per tile, matrix steps over the rest;
+# (2, 4, 4), (8, 4) and (32,) = 32 -> the rest from the per-member table.
+@pytest.mark.parametrize("tail", [(4, 3, 3), (2, 4, 4), (8, 4), (32,), (3, 16)])
+@pytest.mark.parametrize("P,hidden,E", [(7, [30], 11), (9, [64], 3), (12, [100], 2), (14, [64, 64], 4),
+                                        (14, [128, 128], 1), (20, [64, 64], 8), (23, [33, 31], 2)])
+def test_predict_all_layer1_shortcuts(P, hidden, E, tail):
+    for pow2 in (False, True):
+        w = wl.many_params(P, hidden, E, seed=300 + P + sum(tail), pow2=pow2, tail=tail)
+        n = w.space.n_configs
+        assert n <= 1 << 32
+        count = min(n, 15013)
+        begin = min((n // 5) | 1, n - count)       # odd: the first tile starts before the range
+        _check_range(w, begin, count)
+
+
 def test_predict_all_ragged_and_empty_ranges():
     w = wl.conv_shaped()
     sw = sweep_for(w, k=0)

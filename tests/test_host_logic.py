@@ -204,6 +204,25 @@ def test_which_parameters_are_constant_over_a_tile():
     assert hoisted(wl.large(), precision=T.TUNER_BF16_MFMA) == 0
 
 
+def test_which_parameters_come_from_the_table():
+    """When the parameters that vary inside a tile span exactly 32 configurations, their layer-1
+    share is tabulated per member, provided the larger members still fit LDS resident or as
+    two stage buffers."""
+    def tabulated(w, **kw):
+        h = make_space(w.space)
+        return T.tuner_tabulated_parameters(h, T.ModelHandle(w.model.n_members, w.model.widths, _FakeWeights(), **kw))
+    assert tabulated(wl.large()) == 5              # 2^27: five boolean parameters = 32 configurations
+    assert tabulated(wl.streamed()) == 5
+    assert tabulated(wl.paper_convolution()) == 5
+    assert tabulated(wl.wide()) == 0               # 128-wide members: the table would cost a stage buffer
+    assert tabulated(wl.conv_shaped()) == 0        # low strides 12, 6, 3, 1: the pattern does not repeat
+    assert tabulated(wl.paper_stereo()) == 0       # the low parameters span 288
+    assert tabulated(wl.tiny()) == 0
+    assert tabulated(wl.large(), algo=T.TUNER_ALGO_SPLIT16) == 0
+    with pytest.raises(T.TunerError):
+        tabulated(wl.large(), precision=7)
+
+
 def test_tuner_stage_argument_errors_before_any_gpu_work():
     """Sampler, training, list evaluation, metric and second-stage entry points reject bad
     calls on the host (no HIP call is reached)."""

@@ -378,12 +378,15 @@ def random_small(seed: int, max_configs: int = 1024, n_hidden_layers: int = 1,
 
 
 def many_params(n_params: int, widths_hidden: Sequence[int], n_members: int, seed: int,
-                k: int = 50, pow2: bool = False) -> Workload:
+                k: int = 50, pow2: bool = False, tail: Sequence[int] = ()) -> Workload:
     """A space with many parameters (radices 3, 5, 2, 2, ... or all 2) to reach
-    the wider input paddings of the kernels; one random small-integer rule."""
+    the wider input paddings of the kernels; one random small-integer rule.
+    `tail` replaces the radices of the last parameters (how many configurations the
+    fastest parameters span decides how the sweep evaluates layer 1)."""
     radices = [2] * n_params
     if n_params > 29:
         pow2 = True           # 45 * 2**(P-3) would exceed 2**32
+    radices[n_params - len(tail):] = list(tail)
     if not pow2:
         radices[0] = 3
         if n_params > 1:
@@ -396,7 +399,8 @@ def many_params(n_params: int, widths_hidden: Sequence[int], n_members: int, see
     total = sum(radices)
     terms = (st.integers(total, 5).astype(np.int64) - 2).astype(np.int32)[None, :]
     bounds = np.array([n_params // 3], np.int64)
-    sp = Space(f"many-{n_params}-{'pow2' if pow2 else 'mixed'}", values, scales, terms, bounds)
+    sp = Space(f"many-{n_params}-{'pow2' if pow2 else 'mixed'}{'-tail' + 'x'.join(map(str, tail)) if tail else ''}",
+               values, scales, terms, bounds)
     return Workload(sp.name, sp, make_model([n_params, *widths_hidden, 1], n_members, seed), k)
 
 
