@@ -38,17 +38,13 @@ __device__ __forceinline__ void sigmoid16(floatx16& a) {
 
 // Everything after the layer-1 pre-activations (scaled by -log2 e) are in a1: sigmoid,
 // second hidden layer if any, output layer.  Returns the lane's share of the output.
+// LDS reads are issued one step ahead of their use (the next layer's biases and first
+// weights before a sigmoid pass, each group of weights before the matrix steps of the
+// previous group), so that a wave is never left waiting for a read it has just issued.
 template <int NT1, int NT2>
 __device__ __forceinline__ float f32_after_layer1(const float* __restrict__ w, floatx16 (&a1)[NT1], int lane,
                                                   const NetOffsets& o) {
   const int h = lane >> 5;
-  // fp32 MFMA and VALU work do not overlap on a SIMD, so nothing is gained by
-  // interleaving the sigmoid with the matrix instructions
-  __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-  for (int t = 0; t < NT1; ++t) sigmoid16(a1[t]);
-  __builtin_amdgcn_sched_barrier(0);
-
   float part = 0.0f;
   if constexpr (NT2 > 0) {
     floatx16 a2[NT2];
@@ -61,19 +57,38 @@ __device__ __forceinline__ float f32_after_layer1(const float* __restrict__ w, f
         a2[u][4 * g + 0] = b.x; a2[u][4 * g + 1] = b.y; a2[u][4 * g + 2] = b.z; a2[u][4 * g + 3] = b.w;
       }
     const float4* w2 = reinterpret_cast<const float4*>(w + o.w2);
+    float4 a_next = w2[lane];
+    // fp32 MFMA and VALU work do not overlap on a SIMD, so nothing is gained by
+    // interleaving the sigmoid with the matrix instructions
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int t = 0; t < NT1; ++t) sigmoid16(a1[t]);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int t = 0; t < NT1; ++t)
 #pragma unroll
       for (int g = 0; g < 4; ++g)
 #pragma unroll
         for (int u = 0; u < NT2; ++u) {
-          const float4 a = w2[((u * NT1 + t) * 4 + g) * 64 + lane];
+          const float4 a = a_next;
+          // the weights of the next group (same nesting order: u fastest, then g, then t)
+          const int un = u + 1 < NT2 ? u + 1 : 0;
+          const int gn = un ? g : (g + 1 < 4 ? g + 1 : 0);
+          const int tn = (un || gn) ? t : t + 1;
+          if (tn < NT1) a_next = w2[((un * NT1 + tn) * 4 + gn) * 64 + lane];
           a2[u] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, a1[t][4 * g + 0], a2[u], 0, 0, 0);
           a2[u] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, a1[t][4 * g + 1], a2[u], 0, 0, 0);
           a2[u] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, a1[t][4 * g + 2], a2[u], 0, 0, 0);
           a2[u] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, a1[t][4 * g + 3], a2[u], 0, 0, 0);
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read (the next group's weights)
+          __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);   // then this group's four matrix steps
         }
+    // (kept behind the matrix steps: layer 1's activations still hold their registers there)
+    __builtin_amdgcn_sched_barrier(0);
     const float4* wo = reinterpret_cast<const float4*>(w + o.wo);
+    float4 q[NT2 * 4];
+#pragma unroll
+    for (int x = 0; x < NT2 * 4; ++x) q[x] = wo[x * 2 + h];
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int u = 0; u < NT2; ++u) sigmoid16(a2[u]);
@@ -82,23 +97,28 @@ __device__ __forceinline__ float f32_after_layer1(const float* __restrict__ w, f
     for (int u = 0; u < NT2; ++u)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        const float4 q = wo[(u * 4 + g) * 2 + h];
-        part = fmaf(q.x, a2[u][4 * g + 0], part);
-        part = fmaf(q.y, a2[u][4 * g + 1], part);
-        part = fmaf(q.z, a2[u][4 * g + 2], part);
-        part = fmaf(q.w, a2[u][4 * g + 3], part);
+        part = fmaf(q[u * 4 + g].x, a2[u][4 * g + 0], part);
+        part = fmaf(q[u * 4 + g].y, a2[u][4 * g + 1], part);
+        part = fmaf(q[u * 4 + g].z, a2[u][4 * g + 2], part);
+        part = fmaf(q[u * 4 + g].w, a2[u][4 * g + 3], part);
       }
   } else {
     const float4* wo = reinterpret_cast<const float4*>(w + o.wo);
+    float4 q[NT1 * 4];
+#pragma unroll
+    for (int x = 0; x < NT1 * 4; ++x) q[x] = wo[x * 2 + h];
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int t = 0; t < NT1; ++t) sigmoid16(a1[t]);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int t = 0; t < NT1; ++t)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        const float4 q = wo[(t * 4 + g) * 2 + h];
-        part = fmaf(q.x, a1[t][4 * g + 0], part);
-        part = fmaf(q.y, a1[t][4 * g + 1], part);
-        part = fmaf(q.z, a1[t][4 * g + 2], part);
-        part = fmaf(q.w, a1[t][4 * g + 3], part);
+        part = fmaf(q[t * 4 + g].x, a1[t][4 * g + 0], part);
+        part = fmaf(q[t * 4 + g].y, a1[t][4 * g + 1], part);
+        part = fmaf(q[t * 4 + g].z, a1[t][4 * g + 2], part);
+        part = fmaf(q[t * 4 + g].w, a1[t][4 * g + 3], part);
       }
   }
   return part;

@@ -64,6 +64,18 @@ struct F32HNet {
                                                   const NetOffsets& o, const float* xs, float* zs) {
     const float* w = reinterpret_cast<const float*>(wm);
     const int h = lane >> 5;
+    // the low parameters' weights first, where the register budget allows (the 128-wide
+    // variants run 2 waves per SIMD): their reads are in flight while z_high is summed
+    const float4* w1 = reinterpret_cast<const float4*>(w + o.w1);
+    constexpr int KG = (KSL + 3) / 4;       // groups of 4 steps in the packed layout
+    constexpr bool kEarly = NT1 >= 4;
+    float4 wl[KG][NT1];
+    if constexpr (kEarly) {
+#pragma unroll
+      for (int sg = 0; sg < KG; ++sg)
+#pragma unroll
+        for (int t = 0; t < NT1; ++t) wl[sg][t] = w1[(t * KG + sg) * 64 + lane];
+    }
     // z_high, one unit per lane (kUnits / 64 units per lane for the wide nets)
     {
       const float* wh = w + o.wh;
@@ -107,13 +119,11 @@ struct F32HNet {
       }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
-    const float4* w1 = reinterpret_cast<const float4*>(w + o.w1);
-    constexpr int KG = (KSL + 3) / 4;       // groups of 4 steps in the packed layout
 #pragma unroll
     for (int sg = 0; sg < KG; ++sg) {
 #pragma unroll
       for (int t = 0; t < NT1; ++t) {
-        const float4 a = w1[(t * KG + sg) * 64 + lane];
+        const float4 a = kEarly ? wl[sg][t] : w1[(t * KG + sg) * 64 + lane];
         if (4 * sg + 0 < KSL) a1[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, f.x[(4 * sg + 0) % KSL], a1[t], 0, 0, 0);
         if (4 * sg + 1 < KSL) a1[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, f.x[(4 * sg + 1) % KSL], a1[t], 0, 0, 0);
         if (4 * sg + 2 < KSL) a1[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, f.x[(4 * sg + 2) % KSL], a1[t], 0, 0, 0);

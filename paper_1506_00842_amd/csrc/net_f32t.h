@@ -60,6 +60,16 @@ struct F32TNet {
                                                   const NetOffsets& o, const float* xs, float*) {
     const float* w = reinterpret_cast<const float*>(wm);
     const int h = lane >> 5;
+    // the table first: its reads are in flight while z_high is summed
+    floatx16 a1[NT1];
+    const float4* zl = reinterpret_cast<const float4*>(w + o.w1);
+#pragma unroll
+    for (int t = 0; t < NT1; ++t)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const float4 zv = zl[(t * 4 + g) * 64 + lane];
+        a1[t][4 * g + 0] = zv.x; a1[t][4 * g + 1] = zv.y; a1[t][4 * g + 2] = zv.z; a1[t][4 * g + 3] = zv.w;
+      }
     // this half's terms of z_high for the lane's unit of every tile of units
     float zp[NT1];
 #pragma unroll
@@ -80,15 +90,6 @@ struct F32TNet {
         }
       }
     }
-    floatx16 a1[NT1];
-    const float4* zl = reinterpret_cast<const float4*>(w + o.w1);
-#pragma unroll
-    for (int t = 0; t < NT1; ++t)
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const float4 zv = zl[(t * 4 + g) * 64 + lane];
-        a1[t][4 * g + 0] = zv.x; a1[t][4 * g + 1] = zv.y; a1[t][4 * g + 2] = zv.z; a1[t][4 * g + 3] = zv.w;
-      }
 #pragma unroll
     for (int t = 0; t < NT1; ++t) a1[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(zp[t], 1.0f, a1[t], 0, 0, 0);
     return f32_after_layer1<NT1, NT2>(w, a1, lane, o);
