@@ -25,17 +25,6 @@
 
 namespace tuner {
 
-// sigma on 16 accumulator registers, in three passes (exp2, +1, rcp) so that no
-// instruction waits on the transcendental that precedes it
-__device__ __forceinline__ void sigmoid16(floatx16& a) {
-#pragma unroll
-  for (int v = 0; v < 16; ++v) a[v] = __builtin_amdgcn_exp2f(a[v]);
-#pragma unroll
-  for (int v = 0; v < 16; ++v) a[v] = 1.0f + a[v];
-#pragma unroll
-  for (int v = 0; v < 16; ++v) a[v] = __builtin_amdgcn_rcpf(a[v]);
-}
-
 // Everything after the layer-1 pre-activations (scaled by -log2 e) are in a1: sigmoid,
 // second hidden layer if any, output layer.  Returns the lane's share of the output.
 // LDS reads are issued one step ahead of their use (the next layer's biases and first

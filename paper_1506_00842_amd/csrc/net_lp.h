@@ -106,16 +106,21 @@ struct LpNet {
         for (int jj = 0; jj < 4; ++jj) f.x[pl][kb].w[jj] = 0u;
   }
 
+  // The A operand of one block: NPL planes of 8 sixteen-bit weights per lane
+  struct A4 { uint4 p[NPL]; };
+  static __device__ __forceinline__ A4 load_a(const uint4* __restrict__ wa, int idx0, int plane_stride) {
+    A4 a;
+#pragma unroll
+    for (int pl = 0; pl < NPL; ++pl) a.p[pl] = wa[idx0 + pl * plane_stride];
+    return a;
+  }
   // acc += A * B with 1 (NPL = 1) or 3 (NPL = 2) matrix instructions
-  static __device__ __forceinline__ floatx16 contract(const uint4* __restrict__ wa, int idx0, int plane_stride,
-                                                      const B4& b_hi, const B4& b_lo, floatx16 acc) {
-    const uint4 q0 = wa[idx0];
-    const B4 a0 = {{q0.x, q0.y, q0.z, q0.w}};
+  static __device__ __forceinline__ floatx16 mma(const A4& a, const B4& b_hi, const B4& b_lo, floatx16 acc) {
+    const B4 a0 = {{a.p[0].x, a.p[0].y, a.p[0].z, a.p[0].w}};
     acc = Tr::mfma(a0, b_hi, acc);
     if constexpr (NPL == 2) {
       acc = Tr::mfma(a0, b_lo, acc);
-      const uint4 q1 = wa[idx0 + plane_stride];
-      const B4 a1 = {{q1.x, q1.y, q1.z, q1.w}};
+      const B4 a1 = {{a.p[NPL - 1].x, a.p[NPL - 1].y, a.p[NPL - 1].z, a.p[NPL - 1].w}};
       acc = Tr::mfma(a1, b_hi, acc);
     }
     return acc;
@@ -129,6 +134,10 @@ struct LpNet {
     }
   }
 
+  // LDS reads are issued one step ahead of their use (a block's weights before the matrix
+  // steps of the previous block, the next layer's biases and the output weights before a
+  // sigmoid pass), and each sigmoid runs as three passes over 16 registers so that no
+  // instruction waits on the transcendental before it.
   static __device__ __forceinline__ float forward(const uint32_t* __restrict__ wm, const Feat& f, int lane,
                                                   const NetOffsets& o) {
     const int h = lane >> 5;
@@ -137,64 +146,107 @@ struct LpNet {
 #pragma unroll
     for (int t = 0; t < NT1; ++t) init_bias(b1, t, h, a1[t]);
     const uint4* w1 = reinterpret_cast<const uint4*>(wm + o.w1);
+    {
+      A4 a_next = load_a(w1, lane, NT1 * KB1 * 64);
 #pragma unroll
-    for (int kb = 0; kb < KB1; ++kb)
+      for (int kb = 0; kb < KB1; ++kb)
 #pragma unroll
-      for (int t = 0; t < NT1; ++t)
-        a1[t] = contract(w1, (t * KB1 + kb) * 64 + lane, NT1 * KB1 * 64, f.x[0][kb], f.x[NPL - 1][kb], a1[t]);
+        for (int t = 0; t < NT1; ++t) {
+          const A4 a = a_next;
+          const int tn = t + 1 < NT1 ? t + 1 : 0, kn = tn ? kb : kb + 1;
+          if (kn < KB1) a_next = load_a(w1, (tn * KB1 + kn) * 64 + lane, NT1 * KB1 * 64);
+          a1[t] = mma(a, f.x[0][kb], f.x[NPL - 1][kb], a1[t]);
+        }
+    }
 
     const float4* wo = reinterpret_cast<const float4*>(wm + o.wo);
     float part = 0.0f;
     if constexpr (NT2 == 0) {
+      float4 q[NT1 * 4];
+#pragma unroll
+      for (int x = 0; x < NT1 * 4; ++x) q[x] = wo[x * 2 + h];
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int t = 0; t < NT1; ++t) sigmoid16(a1[t]);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int t = 0; t < NT1; ++t)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          const float4 q = wo[(t * 4 + g) * 2 + h];
-          part = fmaf(q.x, sigmoid_prescaled(a1[t][4 * g + 0]), part);
-          part = fmaf(q.y, sigmoid_prescaled(a1[t][4 * g + 1]), part);
-          part = fmaf(q.z, sigmoid_prescaled(a1[t][4 * g + 2]), part);
-          part = fmaf(q.w, sigmoid_prescaled(a1[t][4 * g + 3]), part);
+          part = fmaf(q[t * 4 + g].x, a1[t][4 * g + 0], part);
+          part = fmaf(q[t * 4 + g].y, a1[t][4 * g + 1], part);
+          part = fmaf(q[t * 4 + g].z, a1[t][4 * g + 2], part);
+          part = fmaf(q[t * 4 + g].w, a1[t][4 * g + 3], part);
         }
       return part;
     } else {
-      // sigmoid, then repack the activations as 16-bit B operands
-      B4 hb[NPL][NT1][2];
-#pragma unroll
-      for (int t = 0; t < NT1; ++t)
-#pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-          for (int jj = 0; jj < 4; ++jj) {
-            const float s0 = sigmoid_prescaled(a1[t][8 * b + 2 * jj]);
-            const float s1 = sigmoid_prescaled(a1[t][8 * b + 2 * jj + 1]);
-            uint32_t hi, lo;
-            pack_pair<T, NPL>(s0, s1, hi, lo);
-            hb[0][t][b].w[jj] = hi;
-            if constexpr (NPL == 2) hb[1][t][b].w[jj] = lo;
-          }
       floatx16 a2[NT2];
       const float4* b2 = reinterpret_cast<const float4*>(wm + o.b2);
 #pragma unroll
       for (int u = 0; u < NT2; ++u) init_bias(b2, u, h, a2[u]);
       const uint4* w2 = reinterpret_cast<const uint4*>(wm + o.w2);
-#pragma unroll
-      for (int t = 0; t < NT1; ++t)
+      A4 a_next = load_a(w2, lane, NT2 * 2 * NT1 * 64);
+      // sigmoid of a 32-unit tile of layer 1, repacked as the 16-bit B operands of its two blocks
+      B4 hb[NPL][NT1][2];
+      auto activate = [&](int t) {
+        sigmoid16(a1[t]);
 #pragma unroll
         for (int b = 0; b < 2; ++b)
 #pragma unroll
-          for (int u = 0; u < NT2; ++u)
-            a2[u] = contract(w2, (u * 2 * NT1 + 2 * t + b) * 64 + lane, NT2 * 2 * NT1 * 64, hb[0][t][b],
-                             hb[NPL - 1][t][b], a2[u]);
+          for (int jj = 0; jj < 4; ++jj) {
+            uint32_t hi, lo;
+            pack_pair<T, NPL>(a1[t][8 * b + 2 * jj], a1[t][8 * b + 2 * jj + 1], hi, lo);
+            hb[0][t][b].w[jj] = hi;
+            if constexpr (NPL == 2) hb[1][t][b].w[jj] = lo;
+          }
+      };
+      __builtin_amdgcn_sched_barrier(0);
+      activate(0);
+      __builtin_amdgcn_sched_barrier(0);
+      // 16-bit matrix instructions run beside the vector ALU: the matrix steps over tile t
+      // are interleaved with the sigmoid of tile t + 1 (one block's steps, then a share of
+      // the vector work)
+      constexpr int kMper = NPL == 2 ? 3 : 1;                 // matrix instructions per block and output tile
+      constexpr int kVper = (NPL == 2 ? 112 : 56) / (2 * NT2);       // vector instructions beside them
+#pragma unroll
+      for (int t = 0; t < NT1; ++t) {
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+          for (int u = 0; u < NT2; ++u) {
+            const A4 a = a_next;
+            const int un = u + 1 < NT2 ? u + 1 : 0;
+            const int bn = un ? b : (b + 1 < 2 ? b + 1 : 0);
+            const int tn = (un || bn) ? t : t + 1;
+            if (tn < NT1) a_next = load_a(w2, (un * 2 * NT1 + 2 * tn + bn) * 64 + lane, NT2 * 2 * NT1 * 64);
+            a2[u] = mma(a, hb[0][t][b], hb[NPL - 1][t][b], a2[u]);
+          }
+        if (t + 1 < NT1) {
+          activate(t + 1);
+#pragma unroll
+          for (int i = 0; i < 2 * NT2; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x100, NPL, 0);     // the next block's weights
+            __builtin_amdgcn_sched_group_barrier(0x008, kMper, 0);   // this block's matrix steps
+            __builtin_amdgcn_sched_group_barrier(0x002, kVper, 0);   // a share of the next tile's sigmoid
+          }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      float4 q[NT2 * 4];
+#pragma unroll
+      for (int x = 0; x < NT2 * 4; ++x) q[x] = wo[x * 2 + h];
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int u = 0; u < NT2; ++u) sigmoid16(a2[u]);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int u = 0; u < NT2; ++u)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          const float4 q = wo[(u * 4 + g) * 2 + h];
-          part = fmaf(q.x, sigmoid_prescaled(a2[u][4 * g + 0]), part);
-          part = fmaf(q.y, sigmoid_prescaled(a2[u][4 * g + 1]), part);
-          part = fmaf(q.z, sigmoid_prescaled(a2[u][4 * g + 2]), part);
-          part = fmaf(q.w, sigmoid_prescaled(a2[u][4 * g + 3]), part);
+          part = fmaf(q[u * 4 + g].x, a2[u][4 * g + 0], part);
+          part = fmaf(q[u * 4 + g].y, a2[u][4 * g + 1], part);
+          part = fmaf(q[u * 4 + g].z, a2[u][4 * g + 2], part);
+          part = fmaf(q[u * 4 + g].w, a2[u][4 * g + 3], part);
         }
       return part;
     }

@@ -107,6 +107,17 @@ __device__ __forceinline__ float sigmoid_prescaled(float z) {
   return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(z));
 }
 
+// sigma on 16 accumulator registers, in three passes (exp2, +1, rcp) so that no
+// instruction waits on the transcendental that precedes it
+__device__ __forceinline__ void sigmoid16(floatx16& a) {
+#pragma unroll
+  for (int v = 0; v < 16; ++v) a[v] = __builtin_amdgcn_exp2f(a[v]);
+#pragma unroll
+  for (int v = 0; v < 16; ++v) a[v] = 1.0f + a[v];
+#pragma unroll
+  for (int v = 0; v < 16; ++v) a[v] = __builtin_amdgcn_rcpf(a[v]);
+}
+
 // Bitonic sort of a[0..n) ascending, n a power of two, by the whole workgroup.
 __device__ inline void bitonic_sort(unsigned long long* a, uint32_t n, int tid, int nthreads) {
   for (uint32_t size = 2; size <= n; size <<= 1) {
