@@ -387,6 +387,7 @@ struct ClassifyParams {
   uint64_t begin, count;
   uint32_t head;              // positions of the range before the caller's first configuration
   uint32_t n_chunks, iter;
+  uint32_t per_block;         // chunks classified by one workgroup (<= 256): few when it also fills outputs
   float* pred;                // predict_all: wholly invalid chunks get their +inf (and mask 0) here
   uint8_t* mask;
   uint32_t* live;
@@ -397,9 +398,9 @@ __global__ void __launch_bounds__(256) classify_kernel(const DevSpace sp, const 
   __shared__ uint8_t s_state[256];
   const bool pow2 = sp.all_pow2 != 0;
   const uint32_t lane = threadIdx.x & 63;
-  for (uint32_t base = blockIdx.x * blockDim.x; base < cp.n_chunks; base += gridDim.x * blockDim.x) {
+  for (uint32_t base = blockIdx.x * cp.per_block; base < cp.n_chunks; base += gridDim.x * cp.per_block) {
     const uint32_t c = base + threadIdx.x;
-    const bool in = c < cp.n_chunks;
+    const bool in = threadIdx.x < cp.per_block && c < cp.n_chunks;
     uint32_t state = CHUNK_ALL_INVALID;
     if (in) {
       const uint64_t t0 = (uint64_t)c * cp.iter;
@@ -426,7 +427,7 @@ __global__ void __launch_bounds__(256) classify_kernel(const DevSpace sp, const 
       __syncthreads();
       s_state[threadIdx.x] = in ? (uint8_t)state : (uint8_t)CHUNK_MIXED;
       __syncthreads();
-      for (uint32_t j = 0; j < blockDim.x; ++j) {
+      for (uint32_t j = 0; j < cp.per_block; ++j) {
         if (s_state[j] != CHUNK_ALL_INVALID) continue;
         const uint64_t t0 = (uint64_t)(base + j) * cp.iter;
         const uint64_t left = cp.count - t0 < (uint64_t)cp.iter ? cp.count - t0 : (uint64_t)cp.iter;
@@ -674,8 +675,11 @@ static int run_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin
       cp.mask = mode == MODE_ALL ? mask : nullptr;
       cp.live = live;
       cp.hdr = hdr;
-      hipLaunchKernelGGL(classify_kernel, dim3(std::min<uint32_t>(1024u, (n_chunks + 255u) / 256u)), dim3(256), 0,
-                         stream, sp->dev, cp);
+      // a workgroup that also fills the outputs of its invalid chunks takes few chunks, so
+      // that the fill is spread over the chip even when the range has only a few thousand
+      cp.per_block = cp.pred ? 16u : 256u;
+      hipLaunchKernelGGL(classify_kernel, dim3(std::min<uint32_t>(1u << 16, (n_chunks + cp.per_block - 1u) / cp.per_block)),
+                         dim3(256), 0, stream, sp->dev, cp);
       TUNER_HIP_TRY(hipGetLastError());
       sw.live = live;
     }
