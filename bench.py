@@ -28,8 +28,8 @@ PEAK_HBM_GBS = 8000.0
 # HBM bytes per sweep launch from rocprofv3 FETCH_SIZE / WRITE_SIZE (KiB per dispatch, scaled
 # by the factors a plain 1 GiB copy gives in the same run: 2.000 and 1.000).  Not
 # measurable from inside this script; the summary of those runs is kept under profiles/.
-TRAFFIC_BYTES = {("cfg3", "topk", "f32-mfma"): (2080.58 * 2.0 + 3045.32) * 1024.0,
-                 ("cfg3", "all", "f32-mfma"): 249326.0 * 1024.0}
+TRAFFIC_BYTES = {("cfg3", "topk", "f32-mfma"): (2111.38 * 2.0 + 4069.60) * 1024.0,
+                 ("cfg3", "all", "f32-mfma"): 250350.0 * 1024.0}
 
 
 def cpu_baseline(w, target_seconds: float = 12.0, blocks: int = 0):
