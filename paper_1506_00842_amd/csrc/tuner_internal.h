@@ -29,6 +29,11 @@ namespace tuner {
 int set_error(int code, const std::string& msg);
 int hip_error(hipError_t e, const char* what);
 
+// Raises a kernel's dynamic-LDS limit to at least `bytes` on the current device.  The
+// driver call is made only when the limit has to grow: it is a host round trip of several
+// microseconds, which a short sweep would pay on every call.
+int allow_dynamic_lds(const void* kernel, int bytes);
+
 // Optional timing of the dominant kernels (HIP events on the caller's stream).
 enum { PROFILE_SWEEP = 0, PROFILE_TRAIN = 1, PROFILE_KINDS = 2 };
 bool profile_on();

@@ -7,6 +7,9 @@
 #include <cmath>
 #include <cstring>
 #include <limits>
+#include <map>
+#include <mutex>
+#include <utility>
 #include <new>
 
 #include "tuner_internal.h"
@@ -23,6 +26,20 @@ int set_error(int code, const std::string& msg) {
 int hip_error(hipError_t e, const char* what) {
   g_error = std::string("HIP error: ") + hipGetErrorString(e) + " in " + what;
   return TUNER_EHIP;
+}
+
+int allow_dynamic_lds(const void* kernel, int bytes) {
+  static std::mutex mu;
+  static std::map<std::pair<int, const void*>, int> granted;   // (device, kernel) -> limit set so far
+  int dev = 0;
+  TUNER_HIP_TRY(hipGetDevice(&dev));
+  std::lock_guard<std::mutex> lock(mu);
+  int& have = granted[std::make_pair(dev, kernel)];
+  if (bytes > have) {
+    TUNER_HIP_TRY(hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes));
+    have = bytes;
+  }
+  return TUNER_OK;
 }
 
 static bool is_pow2(uint64_t v) { return v && !(v & (v - 1)); }

@@ -114,7 +114,44 @@ __global__ void __launch_bounds__(256) prep_kernel(const DevSpace sp, const Prep
 // outputs.  merge_kernel: one pair per workgroup, in place in global memory, for
 // lists too long for LDS.
 // ---------------------------------------------------------------------------
-constexpr uint32_t kWaveMergeMaxKp = 256;    // lists up to this long are merged one pair per wave
+constexpr uint32_t kWaveMergeMaxKp = 512;    // lists up to this long are merged one pair per wave
+
+// One wave merges two sorted lists of 64 * E keys in LDS (A, B) into the 64 * E smallest,
+// sorted, in A.  Lane l holds the keys i = l + 64 r: the steps of the merge network whose
+// partner index differs in r stay inside the lane, the others (strides below 64) exchange
+// registers between lanes; LDS is touched once for the load and once for the store.
+template <int E>
+__device__ __forceinline__ void wave_pair_merge(unsigned long long* A, const unsigned long long* B, uint32_t lane) {
+  constexpr uint32_t kp = 64u * E;
+  unsigned long long v[E];
+#pragma unroll
+  for (int r = 0; r < E; ++r) {
+    const uint32_t i = lane + 64u * r;
+    const unsigned long long a = A[i], b = B[kp - 1 - i];
+    v[r] = a < b ? a : b;
+  }
+#pragma unroll
+  for (int jr = E / 2; jr > 0; jr >>= 1)
+#pragma unroll
+    for (int r = 0; r < E; ++r)
+      if ((r & jr) == 0) {
+        const unsigned long long x = v[r], y = v[r | jr];
+        v[r] = x < y ? x : y;
+        v[r | jr] = x < y ? y : x;
+      }
+#pragma unroll
+  for (int j = 32; j > 0; j >>= 1) {
+    const bool upper = (lane & (uint32_t)j) != 0u;
+#pragma unroll
+    for (int r = 0; r < E; ++r) {
+      const unsigned long long o = __shfl_xor(v[r], j);
+      const bool take = upper ? (o > v[r]) : (o < v[r]);
+      v[r] = take ? o : v[r];
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < E; ++r) A[lane + 64u * r] = v[r];
+}
 
 struct MergeParams {
   unsigned long long* pools;
@@ -146,28 +183,55 @@ __global__ void __launch_bounds__(kMergeThreads) merge_tree_kernel(const MergePa
   auto list_ptr = [&](uint32_t j) -> unsigned long long* {
     return j < mp.n_pool_lists ? mp.pools + (size_t)j * mp.cap : mp.extra;
   };
-  // all lists at once, several loads in flight per thread (a loop over the lists would pay
-  // one memory latency per list)
+  // all lists at once, many loads in flight per thread (a loop over the lists would pay
+  // one memory latency per list): 8 x 16 bytes per thread and round, which covers 32 lists
+  // of 512 keys in one round
   const uint32_t total = slots * kp;
-  for (uint32_t t0 = 0; t0 < total; t0 += 4 * kMergeThreads) {
-    unsigned long long v[4];
+  if ((kp & 1u) == 0u) {
+    const uint32_t kp2 = kp >> 1, total2 = total >> 1;
+    ulonglong2* lds2 = reinterpret_cast<ulonglong2*>(lds);
+    for (uint32_t t0 = 0; t0 < total2; t0 += 8 * kMergeThreads) {
+      ulonglong2 v[8];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const uint32_t t = t0 + q * kMergeThreads + tid;
-      const uint32_t j = t / kp, x = t - j * kp;
-      const uint32_t li = base + j * mp.stride0;
-      v[q] = (t < total && li < mp.n_lists) ? list_ptr(li)[x] : kKeyMax;
+      for (int q = 0; q < 8; ++q) {
+        const uint32_t t = t0 + q * kMergeThreads + tid;
+        const uint32_t j = t / kp2, x = t - j * kp2;
+        const uint32_t li = base + j * mp.stride0;
+        v[q] = make_ulonglong2(kKeyMax, kKeyMax);
+        if (t < total2 && li < mp.n_lists) v[q] = reinterpret_cast<const ulonglong2*>(list_ptr(li))[x];
+      }
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        const uint32_t t = t0 + q * kMergeThreads + tid;
+        if (t < total2) lds2[t] = v[q];
+      }
     }
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const uint32_t t = t0 + q * kMergeThreads + tid;
-      if (t < total) lds[t] = v[q];
+  } else {                                   // kp = 1
+    for (uint32_t t = tid; t < total; t += kMergeThreads) {
+      const uint32_t li = base + t * mp.stride0;
+      lds[t] = li < mp.n_lists ? list_ptr(li)[0] : kKeyMax;
     }
   }
   __syncthreads();
   const uint32_t half = kp >> 1;
-  if (kp <= kWaveMergeMaxKp) {
-    // Short lists: one wave per pair of lists.  A wave's LDS instructions execute in
+  if (kp >= 64 && kp <= kWaveMergeMaxKp) {
+    // Lists of 64 .. 512 keys: one wave per pair of lists, the merge network in registers;
+    // the workgroup meets once per tree level.
+    const uint32_t wave = tid >> 6, lane = tid & 63;
+    for (uint32_t s = 1; s < slots; s <<= 1) {
+      const uint32_t npairs = slots / (2 * s);
+      for (uint32_t m = wave; m < npairs; m += kMergeThreads / 64) {
+        unsigned long long* A = lds + (size_t)(2 * m * s) * kp;
+        const unsigned long long* B = A + (size_t)s * kp;
+        if (kp == 64) wave_pair_merge<1>(A, B, lane);
+        else if (kp == 128) wave_pair_merge<2>(A, B, lane);
+        else if (kp == 256) wave_pair_merge<4>(A, B, lane);
+        else wave_pair_merge<8>(A, B, lane);
+      }
+      __syncthreads();
+    }
+  } else if (kp < 64) {
+    // Shorter lists: one wave per pair of lists.  A wave's LDS instructions execute in
     // program order, so the steps of its merge network need no workgroup barrier, only a
     // compiler fence; the workgroup meets once per tree level.
     const uint32_t wave = tid >> 6, lane = tid & 63;
@@ -713,8 +777,8 @@ static int run_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin
     }
     sw.hoist_offset = (uint32_t)((lds + 15) / 16 * 16);
     lds = (size_t)sw.hoist_offset + (size_t)hoist_bytes;
-    TUNER_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(var->fn),
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    rc = allow_dynamic_lds(reinterpret_cast<const void*>(var->fn), (int)lds);
+    if (rc) return rc;
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
     if (g_profile.on) {
       TUNER_HIP_TRY(hipEventCreate(&ev0));
@@ -739,8 +803,8 @@ static int run_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin
       // in LDS, up to 32 lists per workgroup and launch
       uint32_t max_levels = 0;
       while (max_levels < 5 && (list_bytes << (max_levels + 1)) <= merge_lds_max) ++max_levels;
-      TUNER_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(merge_tree_kernel),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)merge_lds_max));
+      rc = allow_dynamic_lds(reinterpret_cast<const void*>(merge_tree_kernel), (int)merge_lds_max);
+      if (rc) return rc;
       uint32_t live = n_lists, stride = 1;
       while (live > 1) {
         uint32_t levels = 1;

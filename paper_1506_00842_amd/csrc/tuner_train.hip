@@ -647,8 +647,10 @@ int tuner_train_ensemble(const tuner_space* space, int32_t n_members, int32_t hi
   tp.hdr = hdr;
   tp.partials = reinterpret_cast<float*>(ws + L.o_partials);
   tp.poll_limit = options->barrier_poll_limit > 0 ? (uint32_t)options->barrier_poll_limit : tuner::kSpinLimit;
-  TUNER_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(var->fn),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+  {
+    const int rc = tuner::allow_dynamic_lds(reinterpret_cast<const void*>(var->fn), (int)lds);
+    if (rc) return rc;
+  }
   hipEvent_t ev0 = nullptr, ev1 = nullptr;
   if (tuner::profile_on()) {
     TUNER_HIP_TRY(hipEventCreate(&ev0));
