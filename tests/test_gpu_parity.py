@@ -263,6 +263,29 @@ def test_topk_small_spaces_exact_and_band():
             say(f"  {w.name} k={k}: n_found {nf}")
 
 
+def test_topk_every_list_length_of_the_merge_tree():
+    """k from 1 to 4096 on the paper's convolution space (256 workgroup lists + the running
+    result): list lengths 1 .. 32 (wave merge in LDS), 64 .. 512 (pair merge in registers),
+    1024 and more (workgroup-wide merge)."""
+    w = wl.paper_convolution()
+    n = w.space.n_configs
+    oy, ov, _ = oracle.predict_range(w.space, w.model, 0, n, threads=THREADS)
+    for k in (1, 3, 17, 32, 33, 64, 65, 128, 129, 256, 257, 300, 512, 513, 1024, 4096):
+        sw = sweep_for(w, k=k)
+        sw.topk(0, n)
+        torch.cuda.synchronize()
+        gv, gi = sw.topk_host()
+        assert len(gi) == k
+        parity.check_topk(gv, gi, oy, ov, 0, k)
+        # the same space in two disjoint calls, the second merging with the first's result
+        cut = (n // 3) | 1
+        sw.topk(cut, n - cut)
+        sw.topk(0, cut, merge=True)
+        torch.cuda.synchronize()
+        gv2, gi2 = sw.topk_host()
+        assert np.array_equal(gi, gi2) and np.array_equal(gv, gv2)
+
+
 def test_topk_unconstrained_is_the_papers_unmasked_sweep():
     w = wl.conv_shaped()
     wu = wl.Workload("u", w.space.without_constraints(), w.model, w.k)
