@@ -174,7 +174,9 @@ int tuner_tabulated_parameters(const tuner_space* space, const tuner_model* mode
  *                        the running result of earlier calls (values, indices
  *                        and *n_found as this function wrote them, same k) and
  *                        are replaced by the top-k of the union; used to stream
- *                        a large space chunk by chunk, in any chunk order.
+ *                        a large space chunk by chunk, in any chunk order.  The
+ *                        ranges of the merged calls must not overlap (a
+ *                        configuration swept twice would be listed twice).
  *   topk_values_dev      DEVICE, k floats
  *   topk_indices_dev     DEVICE, k uint32
  *   n_found_dev          DEVICE, one int32 = min(k, number of valid
