@@ -50,24 +50,58 @@ struct ValuNet {
     return acc;
   }
 
+  // B units of a layer at a time: B independent accumulator chains hide the latency of the
+  // dependent multiply-adds and of the broadcast reads (rows past the real width are zero in
+  // the packed layout, their output weights too).
+  template <int N, int B>
+  static __device__ __forceinline__ void dot_rows(const float* __restrict__ rows, const float (&v)[N], float (&z)[B]) {
+#pragma unroll
+    for (int jj = 0; jj < N / 4; ++jj) {
+      float4 q[B];
+#pragma unroll
+      for (int r = 0; r < B; ++r) q[r] = reinterpret_cast<const float4*>(rows + r * N)[jj];
+#pragma unroll
+      for (int r = 0; r < B; ++r) z[r] = fmaf(q[r].x, v[4 * jj + 0], z[r]);
+#pragma unroll
+      for (int r = 0; r < B; ++r) z[r] = fmaf(q[r].y, v[4 * jj + 1], z[r]);
+#pragma unroll
+      for (int r = 0; r < B; ++r) z[r] = fmaf(q[r].z, v[4 * jj + 2], z[r]);
+#pragma unroll
+      for (int r = 0; r < B; ++r) z[r] = fmaf(q[r].w, v[4 * jj + 3], z[r]);
+    }
+  }
+
+  // one block of B units of the last hidden layer: pre-activations, sigmoid, output layer
+  template <int N, int B>
+  static __device__ __forceinline__ float last_layer_block(const float* __restrict__ rows, const float* __restrict__ bias,
+                                                           const float* __restrict__ wo, const float (&v)[N], float y) {
+    static_assert(B == 4, "biases and output weights are read four at a time");
+    const float4 b4 = *reinterpret_cast<const float4*>(bias);
+    const float4 q4 = *reinterpret_cast<const float4*>(wo);
+    float z[B] = {b4.x, b4.y, b4.z, b4.w};
+    dot_rows<N, B>(rows, v, z);
+    y = fmaf(q4.x, sigmoid_prescaled(z[0]), y);
+    y = fmaf(q4.y, sigmoid_prescaled(z[1]), y);
+    y = fmaf(q4.z, sigmoid_prescaled(z[2]), y);
+    y = fmaf(q4.w, sigmoid_prescaled(z[3]), y);
+    return y;
+  }
+
   static __device__ __forceinline__ float forward(const uint32_t* __restrict__ wm, const Feat& f, int lane,
                                                   const NetOffsets& o) {
     const float* w = reinterpret_cast<const float*>(wm);
+    constexpr int kBlock = 4;
     float y = 0.0f;
     if constexpr (H2P == 0) {
-      for (int u = 0; u < o.h1; ++u) {
-        const float z = dot_row<PMAX>(w + o.w1 + u * PMAX, f.x, w[o.b1 + u]);
-        y = fmaf(w[o.wo + u], sigmoid_prescaled(z), y);
-      }
+      for (int u = 0; u < o.h1; u += kBlock)
+        y = last_layer_block<PMAX, kBlock>(w + o.w1 + u * PMAX, w + o.b1 + u, w + o.wo + u, f.x, y);
     } else {
       float h1[H1P];
 #pragma unroll
       for (int u = 0; u < H1P; ++u)
         h1[u] = sigmoid_prescaled(dot_row<PMAX>(w + o.w1 + u * PMAX, f.x, w[o.b1 + u]));
-      for (int u = 0; u < o.h2; ++u) {
-        const float z = dot_row<H1P>(w + o.w2 + u * H1P, h1, w[o.b2 + u]);
-        y = fmaf(w[o.wo + u], sigmoid_prescaled(z), y);
-      }
+      for (int u = 0; u < o.h2; u += kBlock)
+        y = last_layer_block<H1P, kBlock>(w + o.w2 + u * H1P, w + o.b2 + u, w + o.wo + u, h1, y);
     }
     return y;
   }
