@@ -293,3 +293,14 @@ def test_binding_fails_loudly_without_the_library(monkeypatch):
     monkeypatch.setattr(T, "LIB_PATH", "/nonexistent/libtuner_hip.so")
     with pytest.raises(ImportError):
         T.load_library()
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The benchmark is a one-GPU program: asking for more exits with a message, before any GPU call."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True,
+                       text=True, timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in (r.stdout + r.stderr)
