@@ -762,7 +762,7 @@ static int run_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin
     // resident ensembles that leave room keep the candidate pool in LDS too
     sw.lds_pool_entries = 0;
     sw.lds_pool_offset = 0;
-    if (mode == MODE_TOPK && sw.n_stages == 1 && sw.dynamic) {   // short ranges: one pool fill at most, the global pool is as good
+    if (mode == MODE_TOPK && sw.n_stages == 1) {
       const size_t weights_bytes = ((size_t)mps * member_bytes + 15) / 16 * 16;
       const size_t room = (size_t)budget > weights_bytes ? (size_t)budget - weights_bytes : 0;
       // the smallest pool that takes 2 k keys and one queue unit: small pools are sorted
