@@ -18,7 +18,8 @@
  *    "DEVICE" pointers are GPU memory owned by the caller (for instance a
  *    PyTorch tensor's data_ptr()) on the device that is current at call time.
  *  - The library allocates no device memory: outputs and the workspace are
- *    caller-allocated.  Work is enqueued on the given HIP stream (a
+ *    caller-allocated (tuner_predict_topk_static brings a fixed device array of
+ *    its own instead of a workspace).  Work is enqueued on the given HIP stream (a
  *    hipStream_t passed as void*, NULL = default stream) and the functions
  *    return without synchronising; results are ready once the stream is.
  *  - Index order of the Cartesian product: parameter 0 is the most significant
@@ -195,6 +196,27 @@ int tuner_predict_topk(const tuner_space* space, const tuner_model* model,
                        int32_t merge_with_existing, float* topk_values_dev,
                        uint32_t* topk_indices_dev, int32_t* n_found_dev, void* workspace_dev,
                        size_t workspace_bytes, void* hip_stream);
+
+/*
+ * tuner_predict_topk for callers that cannot allocate device memory or bring a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, results and errors as tuner_predict_topk
+ * minus the workspace: its place is taken by a device array of
+ * TUNER_STATIC_SCRATCH_BYTES that lives in the library (each GPU the library is
+ * used on holds one copy until the process ends).  The call allocates nothing,
+ * on the host side of the GPU or on the device.
+ *   - A space, model and k whose tuner_workspace_bytes() exceeds
+ *     TUNER_STATIC_SCRATCH_BYTES is refused with TUNER_ETOOLARGE (the message
+ *     gives both sizes); the five benchmark configurations fit.
+ *   - Every call on a GPU uses that GPU's one array: calls that may run at the
+ *     same time on one GPU (different streams, different threads) race.  Calls
+ *     ordered on one stream are safe; nothing needs to be cleared between them.
+ */
+#define TUNER_STATIC_SCRATCH_BYTES (64u << 20)
+int tuner_predict_topk_static(const tuner_space* space, const tuner_model* model,
+                              uint64_t index_begin, uint64_t index_count, int32_t k,
+                              int32_t merge_with_existing, float* topk_values_dev,
+                              uint32_t* topk_indices_dev, int32_t* n_found_dev, void* hip_stream);
 
 /*
  * Sweep of the range writing every prediction (Section 5.3, first paragraph).

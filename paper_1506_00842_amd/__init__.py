@@ -23,6 +23,7 @@ TUNER_SCALE_LINEAR, TUNER_SCALE_LOG2 = 0, 1
 TUNER_FP32, TUNER_BF16_MFMA = 0, 1
 TUNER_ALGO_AUTO, TUNER_ALGO_MFMA, TUNER_ALGO_VALU, TUNER_ALGO_SPLIT16 = 0, 1, 2, 3
 TUNER_MAX_K = 16384
+TUNER_STATIC_SCRATCH_BYTES = 64 << 20
 
 EXPORTS = [
     "tuner_space_create", "tuner_space_destroy", "tuner_space_size", "tuner_space_decode",
@@ -31,7 +32,7 @@ EXPORTS = [
     "tuner_version", "tuner_profile_enable", "tuner_profile_read", "tuner_profile_read_train", "tuner_hoisted_parameters", "tuner_tabulated_parameters",
     "tuner_predict_indices", "tuner_sample_workspace_bytes", "tuner_sample_valid",
     "tuner_train_workspace_bytes", "tuner_train_ensemble", "tuner_mean_relative_error",
-    "tuner_best_of",
+    "tuner_best_of", "tuner_predict_topk_static",
 ]
 
 
@@ -88,6 +89,9 @@ def load_library():
     L.tuner_predict_topk.argtypes = [C.c_void_p, C.POINTER(_Model), C.c_uint64, C.c_uint64,
                                      C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                      C.c_void_p, C.c_size_t, C.c_void_p]
+    L.tuner_predict_topk_static.argtypes = [C.c_void_p, C.POINTER(_Model), C.c_uint64, C.c_uint64,
+                                            C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                            C.c_void_p]
     L.tuner_predict_all.argtypes = [C.c_void_p, C.POINTER(_Model), C.c_uint64, C.c_uint64,
                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
     L.tuner_decode_range.argtypes = [C.c_void_p, C.c_uint64, C.c_uint64, C.c_void_p, C.c_void_p,
@@ -250,6 +254,14 @@ def tuner_predict_topk(space, model, index_begin, index_count, k, merge_with_exi
         space.ptr, C.byref(model.c), int(index_begin), int(index_count), int(k),
         int(merge_with_existing), _dp(topk_values_dev), _dp(topk_indices_dev), _dp(n_found_dev),
         _dp(workspace_dev), workspace_dev.numel() * workspace_dev.element_size(), _stream(stream)))
+
+
+def tuner_predict_topk_static(space, model, index_begin, index_count, k, merge_with_existing,
+                              topk_values_dev, topk_indices_dev, n_found_dev, stream=None):
+    _check(load_library().tuner_predict_topk_static(
+        space.ptr, C.byref(model.c), int(index_begin), int(index_count), int(k),
+        int(merge_with_existing), _dp(topk_values_dev), _dp(topk_indices_dev), _dp(n_found_dev),
+        _stream(stream)))
 
 
 def tuner_predict_all(space, model, index_begin, index_count, predictions_dev, valid_mask_dev,

@@ -20,6 +20,7 @@
 // with -log2(e) folded into the packed weights: sigma(z) = 1 / (1 + 2^(z')).
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <utility>
 #include <vector>
 
@@ -596,6 +597,32 @@ static int choose_shape(const tuner_space* sp, const tuner_model* m, bool hoist_
   }
 }
 
+// ---------------------------------------------------------------------------
+// Scratch of the allocation-free entry point: the workspace of a top-k sweep (header, space
+// tables, packed weights, candidate pools, key list of the running result, live-chunk list)
+// in a file-scope device array.  Every GPU the library runs on holds its own copy at its own
+// address; host code uses the address hipGetSymbolAddress returns for the current device,
+// never the array's name.
+// ---------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[TUNER_STATIC_SCRATCH_BYTES];
+
+static int scratch_address(void** out) {
+  static std::mutex mu;
+  static void* ptr_of_device[64] = {};
+  int dev = 0;
+  TUNER_HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= 64) return set_error(TUNER_EHIP, "device ordinal out of range");
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptr_of_device[dev]) {
+    void* ptr = nullptr;
+    TUNER_HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr) return set_error(TUNER_EHIP, "no device address for the static scratch array");
+    ptr_of_device[dev] = ptr;
+  }
+  *out = ptr_of_device[dev];
+  return TUNER_OK;
+}
+
 static int run_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin, uint64_t count,
                      int mode, int k, int merge, float* values, uint32_t* indices, int32_t* n_found,
                      float* pred, uint8_t* mask, void* ws, size_t ws_bytes, hipStream_t stream,
@@ -856,18 +883,27 @@ using tuner::set_error;
 
 extern "C" {
 
-size_t tuner_workspace_bytes(const tuner_space* space, const tuner_model* model, int32_t k) {
-  if (!space || !model) { set_error(TUNER_EINVAL, "null argument"); return 0; }
-  if (k < 0 || k > TUNER_MAX_K) { set_error(TUNER_ETOOLARGE, "k out of range"); return 0; }
+// Bytes of workspace a sweep of this space, model and k may need (any layout of the packed
+// weights a call can choose).
+static int workspace_need(const tuner_space* space, const tuner_model* model, int32_t k, size_t* need_out) {
+  if (!space || !model) return set_error(TUNER_EINVAL, "null argument");
+  if (k < 0 || k > TUNER_MAX_K) return set_error(TUNER_ETOOLARGE, "k out of range");
   size_t need = 0;
-  for (int level = 0; level <= 2; ++level) {     // a call may use any layout of the packed weights
+  for (int level = 0; level <= 2; ++level) {
     tuner::Shape sh{};
-    if (tuner::make_shape(space, model, &sh, level)) return 0;
+    const int rc = tuner::make_shape(space, model, &sh, level);
+    if (rc) return rc;
     const tuner::Variant* var = tuner::find_variant(sh);
-    if (!var) { set_error(TUNER_ETOOLARGE, "no kernel variant for this model shape"); return 0; }
+    if (!var) return set_error(TUNER_ETOOLARGE, "no kernel variant for this model shape");
     need = std::max(need, tuner::make_layout(sh, k, space->n_configs, var).total);
   }
-  return need;
+  *need_out = need;
+  return TUNER_OK;
+}
+
+size_t tuner_workspace_bytes(const tuner_space* space, const tuner_model* model, int32_t k) {
+  size_t need = 0;
+  return workspace_need(space, model, k, &need) == TUNER_OK ? need : 0;
 }
 
 int tuner_hoisted_parameters(const tuner_space* space, const tuner_model* model, int32_t* n_hoisted) {
@@ -932,6 +968,30 @@ int tuner_predict_topk(const tuner_space* space, const tuner_model* model, uint6
   return tuner::run_sweep(space, model, index_begin, index_count, tuner::MODE_TOPK, k,
                           merge_with_existing ? 1 : 0, topk_values_dev, topk_indices_dev, n_found_dev,
                           nullptr, nullptr, workspace_dev, workspace_bytes, (hipStream_t)hip_stream);
+}
+
+int tuner_predict_topk_static(const tuner_space* space, const tuner_model* model, uint64_t index_begin,
+                              uint64_t index_count, int32_t k, int32_t merge_with_existing,
+                              float* topk_values_dev, uint32_t* topk_indices_dev, int32_t* n_found_dev,
+                              void* hip_stream) {
+  if (!space || !model || !topk_values_dev || !topk_indices_dev || !n_found_dev)
+    return set_error(TUNER_EINVAL, "null argument");
+  if (k < 1) return set_error(TUNER_EINVAL, "k must be >= 1");
+  if (k > TUNER_MAX_K) return set_error(TUNER_ETOOLARGE, "k > TUNER_MAX_K");
+  size_t need = 0;
+  int rc = workspace_need(space, model, k, &need);
+  if (rc) return rc;
+  if (need > (size_t)TUNER_STATIC_SCRATCH_BYTES)
+    return set_error(TUNER_ETOOLARGE,
+                     "this space, model and k need " + std::to_string(need) + " bytes of scratch, more than the " +
+                         std::to_string((size_t)TUNER_STATIC_SCRATCH_BYTES) +
+                         " of the static array: use tuner_predict_topk with a workspace");
+  void* ws = nullptr;
+  rc = tuner::scratch_address(&ws);
+  if (rc) return rc;
+  return tuner::run_sweep(space, model, index_begin, index_count, tuner::MODE_TOPK, k,
+                          merge_with_existing ? 1 : 0, topk_values_dev, topk_indices_dev, n_found_dev,
+                          nullptr, nullptr, ws, (size_t)TUNER_STATIC_SCRATCH_BYTES, (hipStream_t)hip_stream);
 }
 
 int tuner_predict_all(const tuner_space* space, const tuner_model* model, uint64_t index_begin,
