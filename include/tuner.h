@@ -168,6 +168,41 @@ int tuner_hoisted_parameters(const tuner_space* space, const tuner_model* model,
 int tuner_tabulated_parameters(const tuner_space* space, const tuner_model* model, int32_t* n_tabulated);
 
 /*
+ * What a sweep of this range would launch (host only; nothing is enqueued).  The
+ * library cuts the range into tiles of consecutive configurations (Section 5.1:
+ * the space is a Cartesian product, so consecutive indices share their leading
+ * parameter values), tiles into chunks (waves x tiles_per_wave x tile
+ * configurations, one chunk per workgroup at a time) and chunks into units of a
+ * work queue; short ranges get smaller chunks so that every compute unit has work.
+ * Uses the current device's compute-unit count and LDS size, or MI355X's when the
+ * process has no GPU.  k = 0 asks about tuner_predict_all, k >= 1 about
+ * tuner_predict_topk.  Errors as for those calls, minus the workspace.
+ */
+typedef struct {
+  int32_t network;                /* 0 fp32 matrix, 1 bf16 matrix, 2 two-plane f16 matrix, 3 vector ALU */
+  int32_t layer1;                 /* 0 plain; 1 tile-constant parameters once per tile; 2 also the rest from a table */
+  int32_t waves;                  /* waves per workgroup */
+  int32_t tile;                   /* configurations per tile */
+  int32_t variant_tiles_per_wave; /* tiles per wave and chunk the kernel is built for */
+  int32_t tiles_per_wave;         /* ... and the number this range uses */
+  int32_t workgroups;
+  uint32_t n_chunks;
+  int32_t chunks_per_unit;
+  uint32_t n_units;
+  int32_t dynamic_queue;          /* units beyond a workgroup's first come from an atomic counter */
+  int32_t live_chunk_list;        /* a classification pass lists the chunks with a valid configuration */
+  int32_t members_per_stage;      /* networks held in LDS at a time */
+  int32_t n_stages;
+  int32_t double_buffer;          /* the next stage loads while the current one is evaluated */
+  int32_t pool_in_lds;            /* the workgroup's candidate pool lives in LDS */
+  int32_t lds_bytes;              /* dynamic LDS of the sweep kernel */
+  int32_t merge_launches;         /* kernels after the sweep (top-k) */
+  size_t workspace_bytes;         /* workspace the call itself needs (<= tuner_workspace_bytes) */
+} tuner_sweep_plan_info;
+int tuner_sweep_plan(const tuner_space* space, const tuner_model* model, uint64_t index_begin,
+                     uint64_t index_count, int32_t k, tuner_sweep_plan_info* out);
+
+/*
  * Sweep of indices [index_begin, index_begin + index_count) and selection of
  * the k valid configurations with the smallest predictions, ordered by
  * (prediction, then index), ascending (Section 5.3).
@@ -355,9 +390,11 @@ int tuner_best_of(uint64_t m, const float* times_dev, int32_t* best_pos_dev, flo
  * training kernel, with a pair of HIP events on the caller's stream.
  * tuner_profile_read / tuner_profile_read_train wait for the recorded events of
  * their kind, return the summed kernel time in milliseconds and the number of
- * launches, and forget them.  Process-wide, not thread-safe; off by default.
+ * launches, and forget them.  tuner_profile_enable(0) drops whatever was recorded
+ * and not read.  Process-wide, not thread-safe; off by default.
  */
 int tuner_profile_enable(int32_t on);
+int64_t tuner_profile_pending(void);   /* recorded launches not yet read (of both kinds) */
 int tuner_profile_read(double* sweep_ms_total, int64_t* n_sweep_launches);
 int tuner_profile_read_train(double* train_ms_total, int64_t* n_train_launches);
 

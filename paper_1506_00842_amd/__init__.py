@@ -32,7 +32,7 @@ EXPORTS = [
     "tuner_version", "tuner_profile_enable", "tuner_profile_read", "tuner_profile_read_train", "tuner_hoisted_parameters", "tuner_tabulated_parameters",
     "tuner_predict_indices", "tuner_sample_workspace_bytes", "tuner_sample_valid",
     "tuner_train_workspace_bytes", "tuner_train_ensemble", "tuner_mean_relative_error",
-    "tuner_best_of", "tuner_predict_topk_static",
+    "tuner_best_of", "tuner_predict_topk_static", "tuner_sweep_plan", "tuner_profile_pending",
 ]
 
 
@@ -51,6 +51,15 @@ class _Model(C.Structure):
     _fields_ = [("n_members", C.c_int32), ("n_layers", C.c_int32),
                 ("widths", C.POINTER(C.c_int32)), ("weights_dev", C.c_void_p),
                 ("precision", C.c_int32), ("algo", C.c_int32)]
+
+
+class _PlanInfo(C.Structure):
+    _fields_ = [("network", C.c_int32), ("layer1", C.c_int32), ("waves", C.c_int32), ("tile", C.c_int32),
+                ("variant_tiles_per_wave", C.c_int32), ("tiles_per_wave", C.c_int32), ("workgroups", C.c_int32),
+                ("n_chunks", C.c_uint32), ("chunks_per_unit", C.c_int32), ("n_units", C.c_uint32),
+                ("dynamic_queue", C.c_int32), ("live_chunk_list", C.c_int32), ("members_per_stage", C.c_int32),
+                ("n_stages", C.c_int32), ("double_buffer", C.c_int32), ("pool_in_lds", C.c_int32),
+                ("lds_bytes", C.c_int32), ("merge_launches", C.c_int32), ("workspace_bytes", C.c_size_t)]
 
 
 _lib = None
@@ -89,6 +98,8 @@ def load_library():
     L.tuner_predict_topk.argtypes = [C.c_void_p, C.POINTER(_Model), C.c_uint64, C.c_uint64,
                                      C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                      C.c_void_p, C.c_size_t, C.c_void_p]
+    L.tuner_sweep_plan.argtypes = [C.c_void_p, C.POINTER(_Model), C.c_uint64, C.c_uint64, C.c_int32,
+                                   C.POINTER(_PlanInfo)]
     L.tuner_predict_topk_static.argtypes = [C.c_void_p, C.POINTER(_Model), C.c_uint64, C.c_uint64,
                                             C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                             C.c_void_p]
@@ -135,8 +146,22 @@ def tuner_tabulated_parameters(space, model) -> int:
     return int(n.value)
 
 
+def tuner_sweep_plan(space, model, index_begin, index_count, k) -> dict:
+    """What a sweep of this range would launch (host only), as a dict of the struct's fields."""
+    info = _PlanInfo()
+    _check(load_library().tuner_sweep_plan(space.ptr, C.byref(model.c), int(index_begin), int(index_count),
+                                           int(k), C.byref(info)))
+    return {name: int(getattr(info, name)) for name, _ in _PlanInfo._fields_}
+
+
 def tuner_profile_enable(on: bool) -> None:
     _check(load_library().tuner_profile_enable(1 if on else 0))
+
+
+def tuner_profile_pending() -> int:
+    L = load_library()
+    L.tuner_profile_pending.restype = C.c_int64
+    return int(L.tuner_profile_pending())
 
 
 def tuner_profile_read():

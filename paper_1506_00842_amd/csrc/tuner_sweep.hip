@@ -556,6 +556,19 @@ static int device_info(DeviceInfo* out) {
   return TUNER_OK;
 }
 
+// For host-only queries: the current device's attributes when there is a device, else the
+// figures of the GPU this library is written for (MI355X: 256 compute units, 160 KB of LDS).
+static DeviceInfo device_info_or_default() {
+  DeviceInfo di;
+  int n = 0;
+  if (hipGetDeviceCount(&n) == hipSuccess && n > 0 && device_info(&di) == TUNER_OK) return di;
+  (void)hipGetLastError();
+  di.n_cu = kMaxGroups;
+  di.max_lds = kLdsBytesPerWorkgroup;
+  di.ok = true;
+  return di;
+}
+
 // LDS bytes of the hoisting networks' per-wave scratch: the high features of a wave's
 // tiles, and for net_f32h.h one z_high vector.
 static int hoist_scratch_bytes(const Shape& sh, const Variant* var) {
@@ -623,14 +636,37 @@ static int scratch_address(void** out) {
   return TUNER_OK;
 }
 
-static int run_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin, uint64_t count,
-                     int mode, int k, int merge, float* values, uint32_t* indices, int32_t* n_found,
-                     float* pred, uint8_t* mask, void* ws, size_t ws_bytes, hipStream_t stream,
-                     const uint32_t* index_list = nullptr) {
+// Everything a sweep call decides before it touches the device: the network layout and
+// kernel variant, how the range is cut into chunks and queue units, how the ensemble goes
+// through LDS, where the candidate pool lives, and the launches of the merge that follows.
+// Made from host data and two device attributes only, so that a call can fail before its
+// first kernel is enqueued and leave the caller's outputs alone.
+struct SweepPlan {
   Shape sh{};
   const Variant* var = nullptr;
-  int rc = choose_shape(sp, m, !index_list, kLdsBytesPerWorkgroup, &sh, &var);
+  Layout L{};
+  uint64_t begin = 0, count = 0;       // the swept range (extended downwards to a tile boundary when hoisting)
+  uint32_t head = 0;
+  int r_used = 0, iter = 0;
+  uint32_t n_chunks = 0, super = 1, n_units = 0, groups = 0;
+  bool dynamic = false, use_live = false;
+  StagePlan pl{};
+  uint32_t stage_words = 0, lds_entries = 0, lds_pool_entries = 0, lds_pool_offset = 0, hoist_offset = 0;
+  size_t lds = 0;
+  // merge of the workgroups' lists (top-k mode)
+  bool merge_in_lds = false;
+  uint32_t merge_max_levels = 0;
+  size_t merge_lds_max = 0;
+  int merge_launches = 0;
+};
+
+static int plan_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin, uint64_t count, int mode,
+                      int k, bool index_list, const DeviceInfo& di, SweepPlan* out) {
+  SweepPlan& P = *out;
+  int rc = choose_shape(sp, m, !index_list, di.max_lds, &P.sh, &P.var);
   if (rc) return rc;
+  const Shape& sh = P.sh;
+  const Variant* var = P.var;
   if (index_list) {
     if (count > (1ull << 32)) return set_error(TUNER_ETOOLARGE, "more than 2^32 list entries");
   } else if (begin > sp->n_configs || count > sp->n_configs - begin) {
@@ -641,21 +677,167 @@ static int run_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin
   // are masked (outputs are addressed through pointers shifted by the same amount).  A
   // configuration is then evaluated in the same place of the same tile whatever the range,
   // so results do not depend on how a sweep is cut into calls.
-  uint32_t head = 0;
-  if (sh.hoist) {
-    head = (uint32_t)(begin % 32);
-    begin -= head;
-    count += head;
-    if (pred) pred -= head;
-    if (mask) mask -= head;
+  P.head = 0;
+  if (sh.hoist && count > 0) {
+    P.head = (uint32_t)(begin % 32);
+    begin -= P.head;
+    count += P.head;
   }
-  const Layout L = make_layout(sh, k, sp->n_configs, var);
+  P.begin = begin;
+  P.count = count;
+  P.L = make_layout(sh, k, sp->n_configs, var);
+
+  const int n_cu = di.n_cu > 0 ? di.n_cu : 1;
+  const uint32_t max_groups = (uint32_t)std::min(n_cu, kMaxGroups);
+  // tiles per wave and chunk: the variant's R, or fewer when the range is so short that
+  // smaller chunks finish sooner (rounds of chunks over the workgroups x tiles per chunk)
+  int r_used = var->R;
+  {
+    uint64_t best = ~0ull;
+    const uint64_t full = (uint64_t)var->waves * var->R * var->tile;
+    const bool is_short = (count + full - 1) / full < 8ull * max_groups;
+    for (int r = var->R; r >= (is_short ? 1 : var->R); --r) {
+      const uint64_t it = (uint64_t)var->waves * r * var->tile;
+      const uint64_t chunks = (count + it - 1) / it;
+      const uint64_t cost = (chunks + max_groups - 1) / max_groups * (uint64_t)r;
+      if (cost < best) { best = cost; r_used = r; }
+    }
+  }
+  P.r_used = r_used;
+  const int iter = var->waves * r_used * var->tile;
+  P.iter = iter;
+  const uint64_t n_chunks64 = (count + iter - 1) / iter;
+  P.n_chunks = (uint32_t)n_chunks64;   // count <= 2^32, iter >= 256
+  // queue unit: up to kMaxSuper chunks, while every workgroup still gets >= 8 units
+  uint32_t super = 1;
+  while (super < (uint32_t)kMaxSuper && n_chunks64 / (2 * super) >= 8ull * max_groups) super *= 2;
+  // a resident ensemble keeps its candidate pool (2 k keys + one queue unit) in LDS too if
+  // it fits; a smaller unit is worth that
+  if (mode == MODE_TOPK && k > 0) {
+    const size_t hoist_b = (size_t)hoist_scratch_bytes(sh, var);
+    const size_t free_b = (size_t)di.max_lds - kSpaceBytes - 64 - hoist_b;
+    const size_t weights_b = ((size_t)sh.E * sh.member_words * 4 + 15) / 16 * 16;
+    if (weights_b < free_b) {
+      const uint32_t kp2 = 2u * host_next_pow2((uint32_t)k);
+      while (super > 1 && (size_t)host_next_pow2(kp2 + super * (uint32_t)iter) * 8 > free_b - weights_b &&
+             (size_t)host_next_pow2(kp2 + (super / 2) * (uint32_t)iter) * 8 <= free_b - weights_b)
+        super /= 2;
+    }
+  }
+  P.super = super;
+  P.n_units = (uint32_t)((n_chunks64 + super - 1) / super);
+  P.groups = std::min<uint32_t>(P.n_units, max_groups);
+
+  if (P.groups > 0) {
+    const int hoist_bytes = hoist_scratch_bytes(sh, var);
+    P.pl = plan_stages(sh, var, di.max_lds);
+    if (P.pl.mps < 1) return set_error(TUNER_ETOOLARGE, "one packed member does not fit in LDS");
+    const int budget = P.pl.budget, mps = P.pl.mps, member_bytes = sh.member_words * 4;
+    // long ranges take units from the queue counter; constrained ones first get the list
+    // of chunks worth visiting (the list is sized for full chunks)
+    P.dynamic = P.n_units > 8u * P.groups;
+    P.use_live = P.dynamic && !index_list && sp->n_constraints > 0 && r_used == var->R;
+    // the region after the space tables holds a stage of weights and doubles as sort
+    // scratch for the candidate pool: make it large enough for a pool that is compacted
+    // when it reaches 2 k + one queue unit, if the LDS allows
+    P.stage_words = (uint32_t)(mps * sh.member_words);
+    size_t region = (size_t)mps * member_bytes * (P.pl.double_buffer ? 2 : 1);
+    if (mode == MODE_TOPK) {
+      const size_t want = 8ull * host_next_pow2(2u * P.L.kp + super * (uint32_t)iter);
+      if (want > region && want <= (size_t)budget) region = want;
+    }
+    P.lds_entries = (uint32_t)(region / 8);
+    size_t lds = (size_t)kSpaceBytes + region;
+    // resident ensembles that leave room keep the candidate pool in LDS too
+    const int n_stages = (sh.E + mps - 1) / mps;
+    if (mode == MODE_TOPK && n_stages == 1) {
+      const size_t weights_bytes = ((size_t)mps * member_bytes + 15) / 16 * 16;
+      const size_t room = (size_t)budget > weights_bytes ? (size_t)budget - weights_bytes : 0;
+      // the smallest pool that takes 2 k keys and one queue unit: small pools are sorted
+      // more often but much faster, and tighten the threshold sooner
+      const uint32_t entries = host_next_pow2(2u * P.L.kp + super * (uint32_t)iter);
+      if ((size_t)entries * 8 <= room) {
+        P.lds_pool_entries = entries;
+        P.lds_pool_offset = (uint32_t)(kSpaceBytes + weights_bytes);
+        P.lds_entries = (uint32_t)(weights_bytes / 8);
+        lds = (size_t)kSpaceBytes + weights_bytes + (size_t)entries * 8;
+      }
+    }
+    P.hoist_offset = (uint32_t)((lds + 15) / 16 * 16);
+    P.lds = (size_t)P.hoist_offset + (size_t)hoist_bytes;
+    if (P.lds + 64 > (size_t)di.max_lds) return set_error(TUNER_ETOOLARGE, "the sweep's LDS layout does not fit this device");
+  }
+
+  if (mode == MODE_TOPK) {
+    // lists: pool 0..groups-1, then the running result
+    const uint32_t n_lists = P.groups + 1;
+    const size_t list_bytes = (size_t)P.L.kp * 8;
+    P.merge_lds_max = std::min<size_t>((size_t)di.max_lds, 128u << 10);
+    P.merge_in_lds = 2 * list_bytes <= P.merge_lds_max;
+    P.merge_launches = 0;
+    if (P.merge_in_lds) {
+      // in LDS, up to 32 lists per workgroup and launch
+      P.merge_max_levels = 0;
+      while (P.merge_max_levels < 5 && (list_bytes << (P.merge_max_levels + 1)) <= P.merge_lds_max) ++P.merge_max_levels;
+      uint32_t live = n_lists;
+      while (live > 1) {
+        uint32_t levels = 1;
+        while (levels < P.merge_max_levels && (1u << levels) < live) ++levels;
+        live = (live + (1u << levels) - 1) >> levels;
+        ++P.merge_launches;
+      }
+      if (n_lists == 1) P.merge_launches = 1;      // finalize only
+    } else {
+      for (uint32_t n = n_lists; n > 1; n = (n + 1) / 2) ++P.merge_launches;
+      ++P.merge_launches;                          // finalize
+    }
+  }
+  return TUNER_OK;
+}
+
+static int run_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin, uint64_t count,
+                     int mode, int k, int merge, float* values, uint32_t* indices, int32_t* n_found,
+                     float* pred, uint8_t* mask, void* ws, size_t ws_bytes, hipStream_t stream,
+                     const uint32_t* index_list = nullptr) {
+  // ---- everything that can fail comes before the first launch
+  // (argument errors are reported even where there is no device to ask: the plan then uses
+  // MI355X's figures and the device error comes after them)
+  DeviceInfo di;
+  const int dev_rc = device_info(&di);
+  const std::string dev_msg = dev_rc ? std::string(tuner_last_error()) : std::string();
+  if (dev_rc) {
+    di.n_cu = kMaxGroups;
+    di.max_lds = kLdsBytesPerWorkgroup;
+  }
+  SweepPlan P;
+  int rc = plan_sweep(sp, m, begin, count, mode, k, index_list != nullptr, di, &P);
+  if (rc) return rc;
+  const Shape& sh = P.sh;
+  const Variant* var = P.var;
+  const Layout& L = P.L;
   if (!ws || ws_bytes < L.total) return set_error(TUNER_EWORKSPACE, "workspace missing or too small");
   if ((reinterpret_cast<uintptr_t>(ws) & 255) != 0) return set_error(TUNER_EWORKSPACE, "workspace not 256-byte aligned");
-  DeviceInfo di;
-  rc = device_info(&di);
-  if (rc) return rc;
+  if (dev_rc) return set_error(dev_rc, dev_msg);
+  if (P.groups > 0) {
+    rc = allow_dynamic_lds(reinterpret_cast<const void*>(var->fn), (int)P.lds);
+    if (rc) return rc;
+  }
+  if (mode == MODE_TOPK && P.merge_in_lds && P.groups > 0) {
+    rc = allow_dynamic_lds(reinterpret_cast<const void*>(merge_tree_kernel), (int)P.merge_lds_max);
+    if (rc) return rc;
+  }
+  hipEvent_t ev0 = nullptr, ev1 = nullptr;
+  if (g_profile.on && P.groups > 0) {
+    TUNER_HIP_TRY(hipEventCreate(&ev0));
+    const hipError_t e = hipEventCreate(&ev1);
+    if (e != hipSuccess) { (void)hipEventDestroy(ev0); return hip_error(e, "hipEventCreate"); }
+  }
 
+  // outputs are addressed from the start of the (possibly extended) range
+  begin = P.begin;
+  count = P.count;
+  if (pred) pred -= P.head;
+  if (mask) mask -= P.head;
   unsigned char* base = static_cast<unsigned char*>(ws);
   WsHeader* hdr = reinterpret_cast<WsHeader*>(base + L.o_hdr);
   DevSpace* space_dev = reinterpret_cast<DevSpace*>(base + L.o_space);
@@ -681,61 +863,19 @@ static int run_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin
   hipLaunchKernelGGL(prep_kernel, dim3(prep_blocks), dim3(256), 0, stream, sp->dev, pp);
   TUNER_HIP_TRY(hipGetLastError());
 
-  const int n_cu = di.n_cu > 0 ? di.n_cu : 1;
-  const uint32_t max_groups = (uint32_t)std::min(n_cu, kMaxGroups);
-  // tiles per wave and chunk: the variant's R, or fewer when the range is so short that
-  // smaller chunks finish sooner (rounds of chunks over the workgroups x tiles per chunk)
-  int r_used = var->R;
-  {
-    uint64_t best = ~0ull;
-    const uint64_t full = (uint64_t)var->waves * var->R * var->tile;
-    const bool is_short = (count + full - 1) / full < 8ull * max_groups;
-    for (int r = var->R; r >= (is_short ? 1 : var->R); --r) {
-      const uint64_t it = (uint64_t)var->waves * r * var->tile;
-      const uint64_t chunks = (count + it - 1) / it;
-      const uint64_t cost = (chunks + max_groups - 1) / max_groups * (uint64_t)r;
-      if (cost < best) { best = cost; r_used = r; }
-    }
-  }
-  const int iter = var->waves * r_used * var->tile;
-  const uint64_t n_chunks64 = (count + iter - 1) / iter;
-  const uint32_t n_chunks = (uint32_t)n_chunks64;   // count <= 2^32, iter >= 256
-  // queue unit: up to kMaxSuper chunks, while every workgroup still gets >= 8 units
-  uint32_t super = 1;
-  while (super < (uint32_t)kMaxSuper && n_chunks64 / (2 * super) >= 8ull * max_groups) super *= 2;
-  // a resident ensemble keeps its candidate pool (2 k keys + one queue unit) in LDS too if
-  // it fits; a smaller unit is worth that
-  if (mode == MODE_TOPK && k > 0) {
-    const size_t hoist_b = (size_t)hoist_scratch_bytes(sh, var);
-    const size_t free_b = (size_t)di.max_lds - kSpaceBytes - 64 - hoist_b;
-    const size_t weights_b = ((size_t)sh.E * sh.member_words * 4 + 15) / 16 * 16;
-    if (weights_b < free_b) {
-      const uint32_t kp2 = 2u * host_next_pow2((uint32_t)k);
-      while (super > 1 && (size_t)host_next_pow2(kp2 + super * (uint32_t)iter) * 8 > free_b - weights_b &&
-             (size_t)host_next_pow2(kp2 + (super / 2) * (uint32_t)iter) * 8 <= free_b - weights_b)
-        super /= 2;
-    }
-  }
-  const uint32_t n_units = (uint32_t)((n_chunks64 + super - 1) / super);
-  uint32_t groups = std::min<uint32_t>(n_units, max_groups);
-
+  const uint32_t groups = P.groups;
   if (groups > 0) {
-    const int hoist_bytes = hoist_scratch_bytes(sh, var);
-    const StagePlan pl = plan_stages(sh, var, di.max_lds);
-    if (pl.mps < 1) return set_error(TUNER_ETOOLARGE, "one packed member does not fit in LDS");
-    const int budget = pl.budget, mps = pl.mps, member_bytes = sh.member_words * 4;
-    const bool double_buffer = pl.double_buffer;
     SweepParams sw{};
     sw.begin = begin;
     sw.count = count;
-    sw.head = head;
-    sw.n_chunks = n_chunks;
-    sw.n_units = n_units;
-    sw.super = (int32_t)super;
-    sw.r_used = r_used;
+    sw.head = P.head;
+    sw.n_chunks = P.n_chunks;
+    sw.n_units = P.n_units;
+    sw.super = (int32_t)P.super;
+    sw.r_used = P.r_used;
     sw.n_members = sh.E;
-    sw.members_per_stage = mps;
-    sw.n_stages = (sh.E + mps - 1) / mps;
+    sw.members_per_stage = P.pl.mps;
+    sw.n_stages = (sh.E + P.pl.mps - 1) / P.pl.mps;
     sw.member_words = sh.member_words;
     sw.off = NetOffsets{sh.o_w1, sh.o_w2, sh.o_b1, sh.o_b2, sh.o_wo, sh.H1, sh.H2, sh.o_wh, sh.p0};
     sw.mode = mode;
@@ -750,18 +890,16 @@ static int run_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin
     sw.pools = pools;
     sw.pred = pred;
     sw.mask = mask;
-    // long ranges take units from the queue counter; constrained ones first get the list
-    // of chunks worth visiting
-    sw.dynamic = n_units > 8u * groups ? 1 : 0;
+    sw.dynamic = P.dynamic ? 1 : 0;
     sw.live = nullptr;
-    if (sw.dynamic && !index_list && sp->n_constraints > 0 && r_used == var->R) {   // the list is sized for full chunks
+    if (P.use_live) {
       uint32_t* live = reinterpret_cast<uint32_t*>(base + L.o_live);
       ClassifyParams cp{};
       cp.begin = begin;
       cp.count = count;
-      cp.head = head;
-      cp.n_chunks = n_chunks;
-      cp.iter = (uint32_t)iter;
+      cp.head = P.head;
+      cp.n_chunks = P.n_chunks;
+      cp.iter = (uint32_t)P.iter;
       cp.pred = mode == MODE_ALL ? pred : nullptr;
       cp.mask = mode == MODE_ALL ? mask : nullptr;
       cp.live = live;
@@ -769,52 +907,21 @@ static int run_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin
       // a workgroup that also fills the outputs of its invalid chunks takes few chunks, so
       // that the fill is spread over the chip even when the range has only a few thousand
       cp.per_block = cp.pred ? 16u : 256u;
-      hipLaunchKernelGGL(classify_kernel, dim3(std::min<uint32_t>(1u << 16, (n_chunks + cp.per_block - 1u) / cp.per_block)),
+      hipLaunchKernelGGL(classify_kernel, dim3(std::min<uint32_t>(1u << 16, (P.n_chunks + cp.per_block - 1u) / cp.per_block)),
                          dim3(256), 0, stream, sp->dev, cp);
       TUNER_HIP_TRY(hipGetLastError());
       sw.live = live;
     }
-    // the region after the space tables holds a stage of weights and doubles as sort
-    // scratch for the candidate pool: make it large enough for a pool that is compacted
-    // when it reaches 2 k + one queue unit, if the LDS allows
-    sw.double_buffer = double_buffer ? 1 : 0;
-    sw.stage_words = (uint32_t)(mps * sh.member_words);
-    size_t region = (size_t)mps * member_bytes * (double_buffer ? 2 : 1);
-    if (mode == MODE_TOPK) {
-      const size_t want = 8ull * host_next_pow2(2u * L.kp + super * (uint32_t)iter);
-      if (want > region && want <= (size_t)budget) region = want;
-    }
-    sw.lds_entries = (uint32_t)(region / 8);
-    size_t lds = (size_t)kSpaceBytes + region;
-    // resident ensembles that leave room keep the candidate pool in LDS too
-    sw.lds_pool_entries = 0;
-    sw.lds_pool_offset = 0;
-    if (mode == MODE_TOPK && sw.n_stages == 1) {
-      const size_t weights_bytes = ((size_t)mps * member_bytes + 15) / 16 * 16;
-      const size_t room = (size_t)budget > weights_bytes ? (size_t)budget - weights_bytes : 0;
-      // the smallest pool that takes 2 k keys and one queue unit: small pools are sorted
-      // more often but much faster, and tighten the threshold sooner
-      const uint32_t entries = host_next_pow2(2u * L.kp + super * (uint32_t)iter);
-      if ((size_t)entries * 8 <= room) {
-        sw.lds_pool_entries = entries;
-        sw.lds_pool_offset = (uint32_t)(kSpaceBytes + weights_bytes);
-        sw.lds_entries = (uint32_t)(weights_bytes / 8);
-        lds = (size_t)kSpaceBytes + weights_bytes + (size_t)entries * 8;
-      }
-    }
-    sw.hoist_offset = (uint32_t)((lds + 15) / 16 * 16);
-    lds = (size_t)sw.hoist_offset + (size_t)hoist_bytes;
-    rc = allow_dynamic_lds(reinterpret_cast<const void*>(var->fn), (int)lds);
-    if (rc) return rc;
-    hipEvent_t ev0 = nullptr, ev1 = nullptr;
-    if (g_profile.on) {
-      TUNER_HIP_TRY(hipEventCreate(&ev0));
-      TUNER_HIP_TRY(hipEventCreate(&ev1));
-      TUNER_HIP_TRY(hipEventRecord(ev0, stream));
-    }
-    hipLaunchKernelGGL(var->fn, dim3(groups), dim3(var->waves * 64), lds, stream, sw);
+    sw.double_buffer = P.pl.double_buffer ? 1 : 0;
+    sw.stage_words = P.stage_words;
+    sw.lds_entries = P.lds_entries;
+    sw.lds_pool_entries = P.lds_pool_entries;
+    sw.lds_pool_offset = P.lds_pool_offset;
+    sw.hoist_offset = P.hoist_offset;
+    if (ev0) TUNER_HIP_TRY(hipEventRecord(ev0, stream));
+    hipLaunchKernelGGL(var->fn, dim3(groups), dim3(var->waves * 64), P.lds, stream, sw);
     TUNER_HIP_TRY(hipGetLastError());
-    if (g_profile.on) {
+    if (ev0) {
       TUNER_HIP_TRY(hipEventRecord(ev1, stream));
       profile_add(PROFILE_SWEEP, ev0, ev1);
     }
@@ -824,18 +931,12 @@ static int run_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin
     // lists: pool 0..groups-1, then the running result
     const uint32_t n_lists = groups + 1;
     const size_t list_bytes = (size_t)L.kp * 8;
-    const size_t merge_lds_max = std::min<size_t>((size_t)di.max_lds, 128u << 10);
     bool finalized = false;
-    if (2 * list_bytes <= merge_lds_max) {
-      // in LDS, up to 32 lists per workgroup and launch
-      uint32_t max_levels = 0;
-      while (max_levels < 5 && (list_bytes << (max_levels + 1)) <= merge_lds_max) ++max_levels;
-      rc = allow_dynamic_lds(reinterpret_cast<const void*>(merge_tree_kernel), (int)merge_lds_max);
-      if (rc) return rc;
+    if (P.merge_in_lds) {
       uint32_t live = n_lists, stride = 1;
       while (live > 1) {
         uint32_t levels = 1;
-        while (levels < max_levels && (1u << levels) < live) ++levels;
+        while (levels < P.merge_max_levels && (1u << levels) < live) ++levels;
         const uint32_t blocks = (live + (1u << levels) - 1) >> levels;
         MergeParams mp{};
         mp.pools = pools;
@@ -919,15 +1020,64 @@ int tuner_tabulated_parameters(const tuner_space* space, const tuner_model* mode
   if (!space || !model || !n_tabulated) return set_error(TUNER_EINVAL, "null argument");
   tuner::Shape sh{};
   const tuner::Variant* var = nullptr;
-  const int rc = tuner::choose_shape(space, model, true, tuner::kLdsBytesPerWorkgroup, &sh, &var);
+  const int rc = tuner::choose_shape(space, model, true, tuner::device_info_or_default().max_lds, &sh, &var);
   if (rc) return rc;
   *n_tabulated = sh.hoist == 2 ? sh.P - sh.p0 : 0;
   return TUNER_OK;
 }
 
+int tuner_sweep_plan(const tuner_space* space, const tuner_model* model, uint64_t index_begin,
+                     uint64_t index_count, int32_t k, tuner_sweep_plan_info* out) {
+  if (!space || !model || !out) return set_error(TUNER_EINVAL, "null argument");
+  if (k < 0) return set_error(TUNER_EINVAL, "k must be >= 0");
+  if (k > TUNER_MAX_K) return set_error(TUNER_ETOOLARGE, "k > TUNER_MAX_K");
+  tuner::SweepPlan P;
+  const int rc = tuner::plan_sweep(space, model, index_begin, index_count, k > 0 ? tuner::MODE_TOPK : tuner::MODE_ALL,
+                                   k, false, tuner::device_info_or_default(), &P);
+  if (rc) return rc;
+  tuner_sweep_plan_info info{};
+  info.network = P.sh.net;
+  info.layer1 = P.sh.hoist;
+  info.waves = P.var->waves;
+  info.tile = P.var->tile;
+  info.variant_tiles_per_wave = P.var->R;
+  info.tiles_per_wave = P.r_used;
+  info.workgroups = (int32_t)P.groups;
+  info.n_chunks = P.n_chunks;
+  info.chunks_per_unit = (int32_t)P.super;
+  info.n_units = P.n_units;
+  info.dynamic_queue = P.dynamic ? 1 : 0;
+  info.live_chunk_list = P.use_live ? 1 : 0;
+  info.members_per_stage = P.groups ? P.pl.mps : 0;
+  info.n_stages = P.groups ? (P.sh.E + P.pl.mps - 1) / P.pl.mps : 0;
+  info.double_buffer = P.groups && P.pl.double_buffer ? 1 : 0;
+  info.pool_in_lds = P.lds_pool_entries > 0 ? 1 : 0;
+  info.lds_bytes = (int32_t)P.lds;
+  info.merge_launches = P.merge_launches;
+  info.workspace_bytes = P.L.total;
+  *out = info;
+  return TUNER_OK;
+}
+
 int tuner_profile_enable(int32_t on) {
   tuner::g_profile.on = on != 0;
+  if (!on) {
+    // timings nobody read are dropped with their events
+    for (auto& kind : tuner::g_profile.events) {
+      for (auto& ev : kind) {
+        (void)hipEventDestroy(ev.first);
+        (void)hipEventDestroy(ev.second);
+      }
+      kind.clear();
+    }
+  }
   return TUNER_OK;
+}
+
+int64_t tuner_profile_pending(void) {
+  int64_t n = 0;
+  for (auto& kind : tuner::g_profile.events) n += (int64_t)kind.size();
+  return n;
 }
 
 static int profile_read(int kind, double* ms_total, int64_t* n_launches) {

@@ -223,18 +223,19 @@ def test_other_nets_benchmark_workloads(net):
 # The widest one-plane networks (128-wide, bf16) evaluate the two tiles a wave owns in a
 # chunk together (the vector work of one tile between the matrix instructions of the
 # other) whenever both tiles hold a valid configuration; that needs chunks of two tiles
-# per wave, which the library uses from about 2^18 configurations per call on.  Below,
-# the same range is swept in one call (two tiles per wave) and in calls of 2^13 (one
-# tile per wave): parity with the oracle at the bf16 tolerance, and the same bits both ways.
+# per wave, which the library uses for every call of 2^20 configurations or more and for
+# shorter ones whose chunk count suits (tuner_sweep_plan tells).  Below, the same range is
+# swept in one call (two tiles per wave) and in calls of 2^13 (one tile per wave): parity
+# with the oracle at the bf16 tolerance, and the same bits both ways.
 WIDE_BF16_RANGES = [
     # (begin, count): parameter 2 has stride 2^18 and parameter 3 stride 2^15 in this space,
     # and a configuration is valid iff digit 2 <= digit 3 (and digit 0 + digit 1 <= 10): a
     # range of 2^18 from a block with digit 2 = 3 has three invalid and five valid blocks of
     # 2^15, each a run of wholly invalid or wholly valid chunks
-    ((3 << 18) + 4321, (1 << 18) + 777),
-    # across a change of digit 1 with digit 0 + digit 1 = 10 -> 11 (valid -> all invalid),
-    # ragged at both ends
-    ((3 << 24) + (7 << 21) + (5 << 18) + 31, (3 << 18) + 12345),
+    ((3 << 18) + 4321, (1 << 18) - 5),
+    # a long range (work queue and live-chunk list) across a change of digit 1 with
+    # digit 0 + digit 1 = 10 -> 11 (valid -> all invalid), ragged at both ends
+    ((3 << 24) + (7 << 21) + (5 << 18) + 31, (1 << 20) + 777),
 ]
 
 
@@ -243,21 +244,19 @@ def test_wide_bf16_two_tiles_per_wave_against_oracle_and_one_tile_path(begin, co
     import paper_1506_00842_amd as T
     w = wl.wide()
     sw = sweep_for(w, precision=T.TUNER_BF16_MFMA)
-    if hasattr(T, "tuner_sweep_plan"):
-        plan = T.tuner_sweep_plan(sw.space, sw.model, begin, count, 0)
-        assert plan["tiles_per_wave"] == plan["variant_tiles_per_wave"] == 2, plan
-        say("wide bf16", begin, count, plan)
+    plan = T.tuner_sweep_plan(sw.space, sw.model, begin, count, 0)
+    assert plan["tiles_per_wave"] == plan["variant_tiles_per_wave"] == 2, plan
+    say("wide bf16", begin, count, plan)
     pred, mask = sw.predict_all(begin, count)
     torch.cuda.synchronize()
     oy, ov, _ = oracle.predict_range(w.space, w.model, begin, count, threads=THREADS)
     assert np.array_equal(mask.cpu().numpy(), ov)
-    assert 0.2 < ov.mean() < 0.8                       # both kinds of chunks are in the range
+    assert 0.15 < ov.mean() < 0.85                     # both kinds of chunks are in the range
     worst, rel = parity.check_predictions(pred.cpu().numpy(), oy, ov, tol=TOL_BF16)
     say(f"  one call: worst {worst:.3f} x tol(1e-2), pure-relative worst {rel:.2e}")
     # the same range in pieces of 2^13 configurations: one tile per wave, plain forward()
     piece = 1 << 13
-    if hasattr(T, "tuner_sweep_plan"):
-        assert T.tuner_sweep_plan(sw.space, sw.model, begin, piece, 0)["tiles_per_wave"] == 1
+    assert T.tuner_sweep_plan(sw.space, sw.model, begin, piece, 0)["tiles_per_wave"] == 1
     pred2 = torch.empty_like(pred)
     mask2 = torch.empty_like(mask)
     for t0 in range(0, count, piece):
@@ -477,3 +476,26 @@ def test_topk_and_predict_all_replay_from_a_hip_graph():
         gv, gi = sw.topk_host()
         assert np.array_equal(gv, ref_v) and np.array_equal(gi, ref_i), f"replay {rep}"
         assert torch.equal(pred, ref_pred), f"replay {rep}"
+
+
+def test_profile_events_recorded_and_dropped():
+    """Sweep timings are kept as pairs of events until they are read; switching profiling
+    off drops the ones nobody read."""
+    import paper_1506_00842_amd as T
+    w = wl.conv_shaped()
+    sw = sweep_for(w)
+    T.tuner_profile_enable(True)
+    try:
+        T.tuner_profile_read()
+        for _ in range(3):
+            sw.topk(0, w.space.n_configs)
+        sw.topk(5, 0)                                 # an empty range launches no sweep
+        assert T.tuner_profile_pending() == 3
+        ms, n = T.tuner_profile_read()
+        assert n == 3 and 0.0 < ms < 1000.0 and T.tuner_profile_pending() == 0
+        sw.topk(0, w.space.n_configs)
+        assert T.tuner_profile_pending() == 1
+    finally:
+        T.tuner_profile_enable(False)
+    assert T.tuner_profile_pending() == 0
+    torch.cuda.synchronize()

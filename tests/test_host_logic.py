@@ -187,6 +187,86 @@ def test_predict_argument_errors_before_any_gpu_work():
     assert L.tuner_decode_range(None, 0, 1, None, None, None, None) == T.TUNER_EINVAL
 
 
+def test_sweep_plan_of_the_benchmark_configurations():
+    """How the library would cut a sweep into chunks and launches (no GPU here: the plan uses
+    MI355X's 256 compute units and 160 KB of LDS)."""
+    def plan(w, begin, count, k, **kw):
+        h = make_space(w.space)
+        return T.tuner_sweep_plan(h, T.ModelHandle(w.model.n_members, w.model.widths, _FakeWeights(), **kw),
+                                  begin, count, k)
+    w = wl.large()
+    p = plan(w, 0, 1 << 27, 1000)
+    assert p["network"] == 0 and p["layer1"] == 2 and p["waves"] == 16 and p["tile"] == 32
+    assert p["tiles_per_wave"] == p["variant_tiles_per_wave"] == 2
+    assert p["workgroups"] == 256 and p["n_chunks"] == (1 << 27) // 1024
+    assert p["dynamic_queue"] == 1 and p["live_chunk_list"] == 1
+    assert p["n_stages"] == 1 and p["members_per_stage"] == 4 and p["pool_in_lds"] == 1
+    assert p["lds_bytes"] <= 160 * 1024 - 64
+    assert p["workspace_bytes"] <= T.tuner_workspace_bytes(
+        make_space(w.space), T.ModelHandle(4, w.model.widths, _FakeWeights()), 1000)
+    p = plan(w, 0, 1 << 27, 0)                       # predict_all: no merge, no pool
+    assert p["merge_launches"] == 0 and p["pool_in_lds"] == 0
+    # the wide network streams one member at a time through two LDS buffers
+    ww = wl.wide()
+    p = plan(ww, 0, 1 << 27, 1000)
+    assert p["layer1"] == 1 and p["waves"] == 8 and p["members_per_stage"] == 1 and p["n_stages"] == 16
+    assert p["double_buffer"] == 1 and p["pool_in_lds"] == 0
+    # bf16, 128 wide: two tiles per wave for calls of 2^20 configurations or more; shorter
+    # calls take whichever of one or two gives fewer rounds of chunks over the 256 workgroups
+    for count, r in ((1 << 27, 2), ((1 << 20) + 777, 2), ((1 << 18) - 5, 2), ((1 << 18) + 777, 1),
+                     (1 << 14, 1), (1 << 13, 1), (12007, 1)):
+        p = plan(ww, 0 if count == 1 << 27 else 3 << 18, count, 0, precision=T.TUNER_BF16_MFMA)
+        assert p["network"] == 1 and p["variant_tiles_per_wave"] == 2 and p["tiles_per_wave"] == r, (count, p)
+    assert p["members_per_stage"] == 2 and p["double_buffer"] == 1
+    # the streamed space: chunks of 2^28, two members per stage
+    ws = wl.streamed()
+    p = plan(ws, 5 << 28, 1 << 28, 4096)
+    assert p["layer1"] == 2 and p["members_per_stage"] == 2 and p["n_stages"] == 4 and p["double_buffer"] == 1
+    assert p["live_chunk_list"] == 1
+    # a short sweep (the paper's convolution space): one chunk per workgroup, no queue, no list
+    wc = wl.paper_convolution()
+    p = plan(wc, 0, wc.space.n_configs, 200)
+    assert p["tiles_per_wave"] == 1 and p["workgroups"] == 256 and p["n_units"] == 256
+    assert p["dynamic_queue"] == 0 and p["live_chunk_list"] == 0
+    # an empty range launches no sweep
+    p = plan(wc, 77, 0, 200)
+    assert p["workgroups"] == 0 and p["n_chunks"] == 0
+    # errors of the calls it describes
+    with pytest.raises(T.TunerError) as e:
+        plan(wc, wc.space.n_configs - 5, 6, 200)
+    assert e.value.code == T.TUNER_EINVAL
+    with pytest.raises(T.TunerError) as e:
+        plan(wc, 0, 10, T.TUNER_MAX_K + 1)
+    assert e.value.code == T.TUNER_ETOOLARGE
+
+
+def test_static_scratch_entry_point_argument_errors():
+    L = T.load_library()
+    w = wl.large()
+    h = make_space(w.space)
+    m = T.ModelHandle(4, w.model.widths, _FakeWeights())
+    fake = C.c_void_p(0x2000)
+    assert L.tuner_predict_topk_static(h.ptr, C.byref(m.c), 0, 256, 10, 0, None, fake, fake, None) == T.TUNER_EINVAL
+    assert L.tuner_predict_topk_static(h.ptr, C.byref(m.c), 0, 256, 0, 0, fake, fake, fake, None) == T.TUNER_EINVAL
+    assert L.tuner_predict_topk_static(h.ptr, C.byref(m.c), 0, 256, T.TUNER_MAX_K + 1, 0, fake, fake, fake, None) == T.TUNER_ETOOLARGE
+    # k = 16384 needs 128 MiB of candidate pools: more than the static array
+    assert T.tuner_workspace_bytes(h, m, 16384) > T.TUNER_STATIC_SCRATCH_BYTES
+    assert L.tuner_predict_topk_static(h.ptr, C.byref(m.c), 0, 256, 16384, 0, fake, fake, fake, None) == T.TUNER_ETOOLARGE
+    assert "static" in T.tuner_last_error() and str(T.TUNER_STATIC_SCRATCH_BYTES) in T.tuner_last_error()
+    bad = T.ModelHandle(4, [13, 64, 64, 1], _FakeWeights())
+    assert L.tuner_predict_topk_static(h.ptr, C.byref(bad.c), 0, 256, 10, 0, fake, fake, fake, None) == T.TUNER_EINVAL
+    hdr = open(os.path.join(ROOT, "include", "tuner.h")).read()
+    assert re.search(r"#define TUNER_STATIC_SCRATCH_BYTES \(64u << 20\)", hdr)
+    assert T.TUNER_STATIC_SCRATCH_BYTES == 64 << 20
+
+
+def test_profile_events_are_dropped_when_profiling_is_switched_off():
+    T.tuner_profile_enable(True)
+    assert T.tuner_profile_pending() == 0
+    T.tuner_profile_enable(False)
+    assert T.tuner_profile_pending() == 0
+
+
 def test_which_parameters_are_constant_over_a_tile():
     """The fp32 matrix network takes the layer-1 share of the leading parameters whose stride
     is a multiple of 32 out of the matrix instructions when at most 8 parameters remain."""
