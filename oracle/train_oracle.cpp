@@ -38,6 +38,7 @@
 #include <unordered_set>
 #include <vector>
 
+#include "oracle_api.h"
 #include "oracle_space.h"
 
 namespace {

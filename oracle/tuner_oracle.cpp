@@ -30,8 +30,11 @@
 //
 // Pins (tests/test_oracle_*.py): space sizes printed in the paper, closed
 // forms for decode/features/zero-weight nets/one-unit nets, analytic valid
-// counts, numpy matrix algebra over an itertools.product enumeration, and
-// brute-force full sorts on spaces of at most 1024 configurations.
+// counts, numpy matrix algebra over an itertools.product enumeration (for the
+// list evaluation: at scattered indices with digits from plain divmod), and
+// brute-force full sorts on spaces of at most 1024 configurations.  A build
+// with AddressSanitizer and UndefinedBehaviorSanitizer runs every entry point
+// (sanitize_driver.cpp).
 // Not pinned: accuracy of a *trained* model (needs the paper's measurements).
 
 #include <algorithm>
@@ -44,6 +47,7 @@
 #include <utility>
 #include <vector>
 
+#include "oracle_api.h"
 #include "oracle_space.h"
 
 namespace {

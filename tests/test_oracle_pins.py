@@ -348,6 +348,70 @@ def test_threaded_driver_equals_single_thread():
         assert np.array_equal(x, y)
 
 
+# ------------------------------------------------- evaluation at a list -------
+def _digits_by_divmod(sp, idx):
+    digs = np.zeros((len(idx), sp.n_params), np.int64)
+    q = np.asarray(idx, dtype=np.uint64).astype(object)        # Python integers: no 64-bit surprises
+    for p in range(sp.n_params - 1, -1, -1):
+        r = int(sp.radices[p])
+        digs[:, p] = [int(v) % r for v in q]
+        q = np.array([int(v) // r for v in q], dtype=object)
+    return digs
+
+
+@pytest.mark.parametrize("maker,n_list", [(wl.conv_shaped, 3000), (wl.large, 2000), (wl.streamed, 1500),
+                                          (wl.paper_raycasting, 2500)])
+def test_predict_indices_against_numpy_algebra_at_scattered_indices(maker, n_list):
+    """The list evaluation (used to judge every index a top-k sweep returns) against numpy
+    matrix algebra with digits from plain divmod, at indices scattered over the whole space,
+    unsorted, with repeats, for one and several threads."""
+    w = maker()
+    sp, m = w.space, w.model
+    n = sp.n_configs
+    st = wl.Stream(99)
+    idx = st.integers(n_list, n).astype(np.uint64)
+    idx[::7] = idx[3]                                          # repeats
+    idx[:4] = [0, n - 1, 1, n - 2]                             # the ends of the space
+    digs = _digits_by_divmod(sp, idx)
+    vals = np.stack([np.array(sp.values[p])[digs[:, p]] for p in range(sp.n_params)], axis=1)
+    ok = numpy_valid(sp, digs)
+    assert ok.any() and (~ok).any()                            # valid and invalid entries in the list
+    ref = numpy_predict(sp, m, numpy_features(sp, vals))
+    for threads in (1, 3, 16):
+        y, v = oracle.predict_indices(sp, m, idx, threads=threads)
+        assert np.array_equal(v.astype(bool), ok)
+        assert np.all(np.isposinf(y[~ok]))
+        assert np.all(np.abs(y[ok] - ref[ok]) <= np.spacing(np.abs(ref[ok])))
+        if threads == 1:
+            y1 = y
+        assert np.array_equal(y, y1)                           # the thread split changes nothing
+
+
+def test_predict_indices_equals_predict_range():
+    w = wl.conv_shaped()
+    sp, m = w.space, w.model
+    begin, count = 5 * 49152 + 6 * 6144 - 10000, 20011       # wg_x = 32, wg_y from 32 into 64: valid, then not
+    ry, rv, _ = oracle.predict_range(sp, m, begin, count)
+    ar = np.arange(begin, begin + count, dtype=np.uint64)
+    for threads in (1, 4):
+        y, v = oracle.predict_indices(sp, m, ar, threads=threads)                 # the range as a list
+        assert np.array_equal(y, ry) and np.array_equal(v, rv)
+    perm = np.argsort(wl.Stream(5).uniform(count))                                # shuffled
+    y, v = oracle.predict_indices(sp, m, ar[perm], threads=3)
+    assert np.array_equal(y, ry[perm]) and np.array_equal(v, rv[perm])
+    rep = np.concatenate([ar[:100], ar[:100], ar[50:60]])                         # repeats
+    y, v = oracle.predict_indices(sp, m, rep, threads=2)
+    assert np.array_equal(y, np.concatenate([ry[:100], ry[:100], ry[50:60]]))
+    inv = ar[rv == 0][:50]                                                        # invalid ones only
+    assert len(inv) == 50
+    y, v = oracle.predict_indices(sp, m, inv, threads=2)
+    assert np.all(np.isposinf(y)) and not v.any()
+    y, v = oracle.predict_indices(sp, m, np.zeros(0, np.uint64), threads=4)       # empty list
+    assert len(y) == 0 and len(v) == 0
+    y, v = oracle.predict_indices(sp, m, ar[:3], threads=16)                      # more threads than entries
+    assert np.array_equal(y, ry[:3])
+
+
 # ------------------------------------------------------------------- P11 -----
 @pytest.mark.parametrize("seed", [1, 2, 3, 4, 5, 6])
 def test_topk_brute_force(seed):
@@ -428,3 +492,16 @@ def test_generator_is_reproducible():
     assert abs(float(W1.std()) - 1 / math.sqrt(14)) < 0.02
     assert wl.wide().model.macs_per_config == 292864
     assert wl.streamed().model.macs_per_config == 43520
+
+
+# ------------------------------------------------------------ sanitizers -----
+def test_oracle_runs_clean_under_address_and_undefined_behaviour_sanitizers():
+    """Every oracle entry point on the 256-configuration space in a build with
+    -fsanitize=address,undefined and no Python in the process (oracle/sanitize_driver.cpp)."""
+    import subprocess
+    from oracle.build import build_sanitized
+    exe = build_sanitized()
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0, r.stdout + r.stderr
+    assert "oracle sanitizer run ok" in r.stdout
+    assert "ERROR" not in r.stderr and "runtime error" not in r.stderr
