@@ -24,46 +24,79 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_FP32_MATRIX_TFLOPS = 157.3   # MI355X published dense fp32 matrix (= fp32 vector) peak
+PEAK_BF16_MATRIX_TFLOPS = 2500.0  # MI355X published dense bf16 matrix peak
 PEAK_HBM_GBS = 8000.0
 # HBM bytes per sweep launch from rocprofv3 FETCH_SIZE / WRITE_SIZE (KiB per dispatch, scaled
-# by the factors a plain 1 GiB copy gives in the same run: 2.000 and 1.000).  Not
-# measurable from inside this script; the summary of those runs is kept under profiles/.
+# by the factors a plain 1 GiB copy gives in the same run: 2.000 and 1.000).  A constant from
+# one profiling run: this script cannot read those counters; the summary of that run is the
+# file named beside the figure.
+TRAFFIC_SOURCE = "profiles/sweep_kernel_f32mfma_cfg3.md"
 TRAFFIC_BYTES = {("cfg3", "topk", "f32-mfma"): (2111.38 * 2.0 + 4069.60) * 1024.0,
                  ("cfg3", "all", "f32-mfma"): 250350.0 * 1024.0}
+CPU_THREADS_CAP = 16              # the host share that goes with one GPU on the benchmark boxes
 
 
-def cpu_baseline(w, target_seconds: float = 12.0, blocks: int = 0):
-    """Times the CPU oracle (as it stands, all host threads through its own range
-    partitioner) on blocks of 4096 indices evenly spaced over the space, so that the
-    sample has the workload's own valid/invalid mix.  A short pilot sizes the sample
-    to about target_seconds.  Returns swept configurations per second."""
+def cpu_model_string() -> str:
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.lower().startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def cpu_baseline(w, single_seconds: float = 5.0, all_seconds: float = 12.0):
+    """Times the CPU oracle as it stands on the host: (1) one thread over a contiguous slice of
+    up to 2^20 indices, (2) all threads (one call = one pool of threads over disjoint index
+    ranges, the oracle's own partitioner) over a contiguous power-of-two slice sized from (1)
+    to about all_seconds, or the whole space if that is shorter.  Slices start in the middle
+    of the space (for the 2^27 spaces: the block of first-parameter digit 4, whose share of
+    valid configurations, 49 %, is close to the space's 47.5 %).  Work per valid configuration
+    is constant, so rates scale linearly to the full space.  Returns swept configurations per
+    second of leg (2) as `value`."""
     import oracle
     sp, m = w.space, w.model
     n = sp.n_configs
-    block = min(n, 1 << 12)
-    n_blocks_total = n // block
-    threads = min(16, os.cpu_count() or 1)
-    oracle.predict_range(sp, m, 0, min(block, 256), threads=1)      # library load, page-in
+    host_cpus = os.cpu_count() or 1
+    try:
+        usable = len(os.sched_getaffinity(0))
+    except AttributeError:
+        usable = host_cpus
+    threads = max(1, min(CPU_THREADS_CAP, usable))
+    oracle.predict_range(sp, m, 0, min(n, 256), threads=1)      # library load, page-in
 
-    def sweep(nb):
-        step = max(1, n_blocks_total // nb)
-        swept = evaluated = 0
+    def pow2_at_most(v):
+        p = 1
+        while p * 2 <= v:
+            p *= 2
+        return p
+
+    def timed(begin, count, nthreads):
         t0 = time.perf_counter()
-        for b in range(nb):
-            _, valid, _ = oracle.predict_range(sp, m, (b * step) * block, block, threads=threads)
-            swept += block
-            evaluated += int(valid.sum())
-        return swept, evaluated, time.perf_counter() - t0
+        _, valid, _ = oracle.predict_range(sp, m, begin, count, threads=nthreads)
+        return time.perf_counter() - t0, int(valid.sum())
 
-    if not blocks:
-        pilot = min(n_blocks_total, 64)
-        _, _, dt = sweep(pilot)
-        blocks = int(max(pilot, min(n_blocks_total, pilot * target_seconds / max(dt, 1e-6))))
-    swept, evaluated, dt = sweep(blocks)
-    return {"value": swept / dt, "unit": "configs/s", "cores": threads, "kind": "oracle",
-            "sample": f"{blocks} blocks of {block} indices evenly spaced over the space "
-                      f"({swept} swept, {evaluated} valid, {dt:.1f} s)",
-            "evaluated_per_s": evaluated / dt}
+    mid = n // 2
+    pilot = min(n, 1 << 13)
+    dt, _ = timed(mid - mid % pilot, pilot, 1)
+    size1 = min(n, 1 << 20, max(pilot, pow2_at_most(int(pilot * single_seconds / max(dt, 1e-6)))))
+    b1 = mid - mid % size1
+    dt1, valid1 = timed(b1, size1, 1)
+    est_all_rate = (size1 / dt1) * threads
+    size_all = n if n / est_all_rate <= 1.5 * all_seconds else max(size1, pow2_at_most(int(est_all_rate * all_seconds)))
+    size_all = min(size_all, n)
+    ba = 0 if size_all == n else mid - mid % size_all
+    dta, valida = timed(ba, size_all, threads)
+    return {"value": size_all / dta, "unit": "configs/s", "cores": threads, "kind": "oracle",
+            "sample": f"one call over the contiguous slice [{ba}, +{size_all}) of the same workload "
+                      f"({valida} valid, {dta:.1f} s, {threads} threads); whole space = {n}",
+            "evaluated_per_s": valida / dta,
+            "single_thread": {"value": size1 / dt1, "unit": "configs/s", "evaluated_per_s": valid1 / dt1,
+                              "sample": f"contiguous slice [{b1}, +{size1}) ({valid1} valid, {dt1:.1f} s)"},
+            "cpu_model": cpu_model_string(), "host_logical_cpus": host_cpus, "usable_cpus": usable,
+            "threads_cap": CPU_THREADS_CAP}
 
 
 PEAK_FP32_VECTOR_FMA_TFLOPS = 78.6   # 256 CUs x 4 SIMDs x 16 lanes x 1 FMA x 2.4 GHz (no packed fp32)
@@ -179,7 +212,8 @@ def main():
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (a kernel of known HBM "
                          "traffic, to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
-    ap.add_argument("--cpu-blocks", type=int, default=0, help="blocks of 4096 indices for the CPU baseline")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="skip the short runs of the other benchmark configurations (default workload only)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (the sweep shards by index range; "
@@ -197,25 +231,12 @@ def main():
     sp, m = w.space, w.model
     N = sp.n_configs
     chunk = w.chunk if w.chunk else N
-    net_kw = {"f32-mfma": dict(precision=T.TUNER_FP32, algo=T.TUNER_ALGO_MFMA),
-              "split16": dict(precision=T.TUNER_FP32, algo=T.TUNER_ALGO_SPLIT16),
-              "valu": dict(precision=T.TUNER_FP32, algo=T.TUNER_ALGO_VALU),
-              "bf16": dict(precision=T.TUNER_BF16_MFMA, algo=T.TUNER_ALGO_AUTO)}[args.net]
-    sw = Sweep(sp, m, w.k if args.mode == "topk" else 0, **net_kw)
+    sw = Sweep(sp, m, w.k if args.mode == "topk" else 0, **net_kwargs(T, args.net))
     stream = torch.cuda.current_stream()
-    pred = mask = None
+    pred = None
     if args.mode == "all":
         pred = torch.empty(chunk, dtype=torch.float32, device=sw.device)
-
-    def step():
-        if args.mode == "topk":
-            first = True
-            for b in range(0, N, chunk):
-                sw.topk(b, min(chunk, N - b), merge=not first, stream=stream)
-                first = False
-        else:
-            for b in range(0, N, chunk):
-                sw.predict_all(b, min(chunk, N - b), want_mask=False, out=pred, stream=stream)
+    step = make_step(sw, N, chunk, args.mode, pred, stream)
 
     if args.copy_calibration_mib:
         src = torch.ones(args.copy_calibration_mib << 18, dtype=torch.float32, device=sw.device)
@@ -229,15 +250,15 @@ def main():
     torch.cuda.synchronize()
     if args.graph:
         side = torch.cuda.Stream()
-        eager_stream, stream = stream, side
+        eager_stream = stream
         side.wait_stream(eager_stream)
+        gstep = make_step(sw, N, chunk, args.mode, pred, side)
         with torch.cuda.stream(side):
-            step()
+            gstep()
         torch.cuda.synchronize()
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph, stream=side):
-            step()
-        stream = eager_stream
+            gstep()
         graph.replay()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -271,77 +292,163 @@ def main():
 
     ms_per_step = 1e3 * dt / args.steps
     n_valid = w.n_valid if w.n_valid >= 0 else None
-    flop_per_cfg = 2 * m.macs_per_config
-    # layer-1 share of the parameters that are constant over a tile of 32 configurations:
-    # computed once per tile, i.e. 31/32 of those multiply-adds are never executed
-    n_hoisted = T.tuner_hoisted_parameters(sw.space, sw.model)
-    executed_flop_per_cfg = flop_per_cfg - 2.0 * m.n_members * m.widths[1] * n_hoisted * 31.0 / 32.0
-    # layer-1 share of the remaining parameters read from a per-member table: no multiply-adds
-    # per configuration but the one matrix step (2 inputs) that adds the tile's vector to the table
-    n_tabulated = T.tuner_tabulated_parameters(sw.space, sw.model) if args.net == "f32-mfma" else 0
-    if n_tabulated:
-        executed_flop_per_cfg -= 2.0 * m.n_members * m.widths[1] * (n_tabulated - 2)
-    launches_per_step = n_launch / args.steps
-    kernel_ms = sweep_ms / max(n_launch, 1)
-    roof = None
-    if n_valid is not None:
-        # the sweep skips tiles with no valid configuration: only evaluated
-        # configurations count as algorithmic flops
-        flops_per_launch = n_valid * flop_per_cfg / launches_per_step
-        achieved = flops_per_launch / (kernel_ms * 1e-3) / 1e12
-        roof = {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP32_MATRIX_TFLOPS,
-                "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MATRIX_TFLOPS,
-                "traffic": TRAFFIC_BYTES.get((args.workload, args.mode, args.net)),
-                "kernel": "sweep_kernel (fp32 MFMA 32x32x2)", "kernel_ms": kernel_ms,
-                "launches_per_step": launches_per_step,
-                "flop_per_config": flop_per_cfg, "evaluated_configs_per_launch": n_valid / launches_per_step,
-                "hoisted_parameters": n_hoisted, "tabulated_parameters": n_tabulated,
-                "executed_flop_per_config": executed_flop_per_cfg,
-                "frac_executed": achieved * executed_flop_per_cfg / flop_per_cfg / PEAK_FP32_MATRIX_TFLOPS,
-                "sigmoids_per_config": m.sigmoids_per_config}
+    roof = roofline_of(T, sw, w, args.net, sweep_ms / max(n_launch, 1), n_launch / args.steps)
+    if roof is not None:
+        tb = TRAFFIC_BYTES.get((args.workload, args.mode, args.net))
+        roof["traffic"] = tb
+        roof["traffic_source"] = (f"{TRAFFIC_SOURCE} (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this command, a "
+                                  "constant from that profiling run, not measured by this one)") if tb else None
     out = {
         "metric": "predicted configs/sec (decode+MLP ensemble+top-k)" if args.mode == "topk"
                   else "predicted configs/sec (decode+MLP ensemble, all predictions written)",
         "value": N / (dt / args.steps), "unit": "configs/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "ms_per_step_no_events": ms_per_step_no_events,
         "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if args.net == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": w.name, "n_configs": N, "n_valid": n_valid, "k": w.k,
                    "members": m.n_members, "widths": list(m.widths), "mode": args.mode,
                    "chunk": chunk, "net": args.net, "hip_graph": bool(args.graph)},
         "roofline": roof,
     }
+    if args.mode == "all":
+        out["hbm_write_GBs"] = 4.0 * N / (dt / args.steps) / 1e9
     if not args.no_other_nets and args.mode == "topk":
         # the same workload with the other network evaluations (3 steps each, outside the
         # timed region above): context for the choice of the matrix-core path
         others = {}
-        for name, kw in (("f32-mfma", dict(algo=T.TUNER_ALGO_MFMA)), ("split16", dict(algo=T.TUNER_ALGO_SPLIT16)),
-                         ("valu", dict(algo=T.TUNER_ALGO_VALU)), ("bf16", dict(precision=T.TUNER_BF16_MFMA))):
+        for name in ("f32-mfma", "split16", "valu", "bf16"):
             if name == args.net:
                 continue
-            sw2 = Sweep(sp, m, w.k, **kw)
-
-            def step2():
-                first = True
-                for b in range(0, N, chunk):
-                    sw2.topk(b, min(chunk, N - b), merge=not first, stream=stream)
-                    first = False
-            step2()
-            torch.cuda.synchronize()
-            t1 = time.perf_counter()
-            for _ in range(3):
-                step2()
-            torch.cuda.synchronize()
-            d2 = (time.perf_counter() - t1) / 3
-            others[name] = {"ms_per_step": 1e3 * d2, "configs_per_s": N / d2,
+            sw2 = Sweep(sp, m, w.k, **net_kwargs(T, name))
+            r = time_steps(T, torch, make_step(sw2, N, chunk, "topk", None, stream), 3, 1)
+            others[name] = {"ms_per_step": r["ms_per_step"], "configs_per_s": N / (r["ms_per_step"] * 1e-3),
                             "tolerance": 1e-2 if name == "bf16" else 1e-5}
             del sw2
         out["other_nets"] = others
-    if args.mode == "all":
-        out["hbm_write_GBs"] = 4.0 * N / (dt / args.steps) / 1e9
+    if not args.no_other_workloads and args.workload == "cfg3" and args.mode == "topk" and args.net == "f32-mfma":
+        out["other_workloads"] = other_workloads(T, torch, wl, Sweep, stream)
     if not args.no_cpu:
-        out["cpu_baseline"] = cpu_baseline(w, blocks=args.cpu_blocks)
+        out["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(out))
+
+
+def net_kwargs(T, net):
+    return {"f32-mfma": dict(precision=T.TUNER_FP32, algo=T.TUNER_ALGO_MFMA),
+            "split16": dict(precision=T.TUNER_FP32, algo=T.TUNER_ALGO_SPLIT16),
+            "valu": dict(precision=T.TUNER_FP32, algo=T.TUNER_ALGO_VALU),
+            "bf16": dict(precision=T.TUNER_BF16_MFMA, algo=T.TUNER_ALGO_AUTO)}[net]
+
+
+def make_step(sw, N, chunk, mode, pred, stream):
+    """One pass of the whole hot path over the whole space (in chunks with a running result
+    for the streamed workload)."""
+    def step():
+        if mode == "topk":
+            first = True
+            for b in range(0, N, chunk):
+                sw.topk(b, min(chunk, N - b), merge=not first, stream=stream)
+                first = False
+        else:
+            for b in range(0, N, chunk):
+                sw.predict_all(b, min(chunk, N - b), want_mask=False, out=pred, stream=stream)
+    return step
+
+
+def time_steps(T, torch, step, steps, warmup):
+    """ms per step (host clock around `steps` steps) and the sweep kernel's own duration (HIP
+    events recorded by the library on the launch stream)."""
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    T.tuner_profile_enable(True)
+    T.tuner_profile_read()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    sweep_ms, n_launch = T.tuner_profile_read()
+    T.tuner_profile_enable(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    return {"ms_per_step": 1e3 * dt / steps, "ms_per_step_no_events": 1e3 * (time.perf_counter() - t0) / steps,
+            "kernel_ms": sweep_ms / max(n_launch, 1), "launches_per_step": n_launch / steps}
+
+
+def roofline_of(T, sw, w, net, kernel_ms, launches_per_step):
+    """The sweep kernel against the matrix peak of its operand type.  Only arithmetic that is
+    executed counts: configurations the sweep skips (invalid ones) count for nothing, and the
+    layer-1 multiply-adds of the parameters that are constant over a tile of 32 configurations
+    count once per tile, those read from the per-member table not at all.  The figure with
+    every evaluated configuration's full network is kept as `frac_algorithmic`."""
+    m = w.model
+    if w.n_valid < 0 or kernel_ms <= 0:
+        return None
+    flop_per_cfg = 2 * m.macs_per_config
+    n_hoisted = T.tuner_hoisted_parameters(sw.space, sw.model)
+    executed = flop_per_cfg - 2.0 * m.n_members * m.widths[1] * n_hoisted * 31.0 / 32.0
+    n_tabulated = T.tuner_tabulated_parameters(sw.space, sw.model) if net == "f32-mfma" else 0
+    if n_tabulated:
+        # one matrix step (2 inputs) adds the tile's vector to the table
+        executed -= 2.0 * m.n_members * m.widths[1] * (n_tabulated - 2)
+    peak = PEAK_BF16_MATRIX_TFLOPS if net == "bf16" else PEAK_FP32_MATRIX_TFLOPS
+    bound = "mfma"
+    if net == "split16":          # three f16 matrix products per fp32 product, against the f16 matrix peak
+        executed *= 3.0
+        peak = PEAK_BF16_MATRIX_TFLOPS
+    elif net == "valu":           # plain vector FMAs, against the unpacked fp32 vector rate
+        bound, peak = "alu", PEAK_FP32_VECTOR_FMA_TFLOPS
+    evaluated_per_launch = w.n_valid / launches_per_step
+    achieved = evaluated_per_launch * executed / (kernel_ms * 1e-3) / 1e12
+    algorithmic = evaluated_per_launch * flop_per_cfg / (kernel_ms * 1e-3) / 1e12
+    return {"bound": bound, "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
+            "traffic": None,
+            "kernel": {"f32-mfma": "sweep_kernel (fp32 MFMA 32x32x2)", "bf16": "sweep_kernel (bf16 MFMA 32x32x16)",
+                       "split16": "sweep_kernel (f16 MFMA 32x32x16, two planes)", "valu": "sweep_kernel (v_fma_f32)"}[net],
+            "kernel_ms": kernel_ms, "launches_per_step": launches_per_step,
+            "evaluated_configs_per_launch": evaluated_per_launch,
+            "executed_flop_per_config": executed, "flop_per_config": flop_per_cfg,
+            "achieved_algorithmic": algorithmic, "frac_algorithmic": algorithmic / peak,
+            "hoisted_parameters": n_hoisted, "tabulated_parameters": n_tabulated,
+            "sigmoids_per_config": m.sigmoids_per_config}
+
+
+def other_workloads(T, torch, wl, Sweep, stream):
+    """The other synthetic spaces of the benchmark definition and the paper's convolution
+    space, a few steps each, outside the timed region of the headline."""
+    res = {}
+
+    def leg(name, w, net, mode, steps, warmup):
+        N = w.space.n_configs
+        chunk = w.chunk if w.chunk else N
+        sw = Sweep(w.space, w.model, w.k if mode == "topk" else 0, **net_kwargs(T, net))
+        pred = torch.empty(chunk, dtype=torch.float32, device=sw.device) if mode == "all" else None
+        r = time_steps(T, torch, make_step(sw, N, chunk, mode, pred, stream), steps, warmup)
+        ms = r["ms_per_step_no_events"] if r["ms_per_step"] < 1.0 else r["ms_per_step"]
+        e = {"workload": w.name, "net": net, "mode": mode, "k": w.k if mode == "topk" else 0,
+             "ms_per_step": ms, "configs_per_s": N / (ms * 1e-3), "sweep_kernel_ms": r["kernel_ms"],
+             "launches_per_step": r["launches_per_step"], "steps": steps}
+        roof = roofline_of(T, sw, w, net, r["kernel_ms"], r["launches_per_step"])
+        if roof is not None and ms >= 1.0:
+            e["frac_of_peak"] = roof["frac"]
+            e["peak_TFLOPs"] = roof["peak"]
+            e["frac_algorithmic"] = roof["frac_algorithmic"]
+        if mode == "all":
+            e["hbm_write_GBs"] = 4.0 * N / (ms * 1e-3) / 1e9
+        res[name] = e
+
+    leg("cfg3-predict_all", wl.large(), "f32-mfma", "all", 5, 1)
+    leg("cfg4-f32", wl.wide(), "f32-mfma", "topk", 3, 1)
+    leg("cfg4-bf16", wl.wide(), "bf16", "topk", 5, 1)
+    leg("cfg5-streamed-16-chunks", wl.streamed(), "f32-mfma", "topk", 2, 1)
+    # short sweeps: latency per call (no roofline fraction: they are bound by fixed costs)
+    leg("cfg1-tiny", wl.tiny(), "f32-mfma", "topk", 200, 20)
+    leg("cfg2-conv-shaped", wl.conv_shaped(), "f32-mfma", "topk", 200, 20)
+    leg("paper-convolution", wl.paper_convolution(), "f32-mfma", "topk", 200, 20)
+    return res
 
 
 if __name__ == "__main__":
