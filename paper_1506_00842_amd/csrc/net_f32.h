@@ -123,7 +123,6 @@ struct F32Net {
   // points that slot of the table at the constant)
   static constexpr bool kBiasInput = true;
   static constexpr bool kHoist = false;
-  static constexpr bool kPair = false;
   static __device__ __forceinline__ void load_features(const DevSpace& sp, uint32_t i, int lane, bool pow2,
                                                        const NetOffsets&, Feat& f) {
     const int h = lane >> 5;

@@ -27,7 +27,6 @@ template <int KSL, int NT1, int NT2>
 struct F32HNet {
   static constexpr int kTile = 32;
   static constexpr bool kHoist = true;
-  static constexpr bool kPair = false;
   static constexpr int kUnits = NT1 * 32;
   static constexpr int kScratchZ = kUnits < 64 ? 64 : kUnits;   // floats of the z_high scratch
   struct Feat { float x[KSL]; };   // B operand of layer 1: feature of parameter p0 + 2 s + h

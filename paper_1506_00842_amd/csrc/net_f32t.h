@@ -35,7 +35,6 @@ template <int NT1, int NT2>
 struct F32TNet {
   static constexpr int kTile = 32;
   static constexpr bool kHoist = true;
-  static constexpr bool kPair = false;
   static constexpr int kUnits = NT1 * 32;
   static constexpr int kScratchZ = 0;      // no z scratch: z_high goes straight into the A operand
   struct Feat {};                          // the low parameters' features are in the table

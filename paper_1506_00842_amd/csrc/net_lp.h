@@ -68,7 +68,13 @@ __device__ __forceinline__ void pack_pair(float a, float b, uint32_t& hi, uint32
   }
 }
 
-template <class T, int NPL, int KB1, int NT1, int NT2>
+// STREAM (two hidden layers only): layer 1 is evaluated one 32-unit tile at a time, each tile
+// going through its sigmoid and into layer 2's accumulators before the next one is computed,
+// so that a wave holds one layer-1 tile instead of all of them (128-wide networks then fit
+// 128 registers, i.e. four waves per SIMD: the 16-bit matrix instructions of one wave run
+// beside the vector work of the others).  Same operations per configuration, in the same
+// order, as the plain evaluation: same bits.
+template <class T, int NPL, int KB1, int NT1, int NT2, bool STREAM = false>
 struct LpNet {
   typedef LpTraits<T> Tr;
   static constexpr int kTile = 32;
@@ -140,6 +146,7 @@ struct LpNet {
   // instruction waits on the transcendental before it.
   static __device__ __forceinline__ float forward(const uint32_t* __restrict__ wm, const Feat& f, int lane,
                                                   const NetOffsets& o) {
+    if constexpr (STREAM && NT2 > 0) return forward_stream(wm, f, lane, o);
     const int h = lane >> 5;
     floatx16 a1[NT1];
     const float4* b1 = reinterpret_cast<const float4*>(wm + o.b1);
@@ -252,145 +259,74 @@ struct LpNet {
     }
   }
 
-  // Two tiles of a wave at once, for the wide one-plane networks (two waves per SIMD, 256
-  // registers each).  The vector work of one tile is dealt out, a few instructions at a time,
-  // between the matrix instructions of the other (layer 2 of tile A with the sigmoid of tile
-  // B's layer 1, layer 2 of tile B with tile A's last sigmoid and output layer), with the
-  // weights read two steps ahead, so that neither pipeline waits for an operand.  Every
-  // tile sees the same operations in the same order as in forward(): same bits.
-  static constexpr bool kPair = NPL == 1 && NT1 >= 4 && NT2 >= 4;
-  static __device__ __forceinline__ void forward2(const uint32_t* __restrict__ wm, const Feat& fA, const Feat& fB,
-                                                  int lane, const NetOffsets& o, float& yA, float& yB) {
+  static __device__ __forceinline__ A4 load_w1(const uint4* __restrict__ w1, int t, int kb, int lane) {
+    return load_a(w1, (t * KB1 + kb) * 64 + lane, NT1 * KB1 * 64);
+  }
+  static __device__ __forceinline__ A4 load_w2(const uint4* __restrict__ w2, int t, int b, int u, int lane) {
+    return load_a(w2, (u * 2 * NT1 + 2 * t + b) * 64 + lane, NT2 * 2 * NT1 * 64);
+  }
+  static __device__ __forceinline__ void pack_tile(const floatx16& a1, B4 (&hb)[NPL][2]) {
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) {
+        uint32_t hi, lo;
+        pack_pair<T, NPL>(a1[8 * b + 2 * jj], a1[8 * b + 2 * jj + 1], hi, lo);
+        hb[0][b].w[jj] = hi;
+        if constexpr (NPL == 2) hb[1][b].w[jj] = lo;
+      }
+  }
+
+  // Layer 1 one 32-unit tile at a time: sigmoid and repacking of tile t, then the layer-1
+  // steps of tile t + 1 (its accumulator is free once tile t is packed, and its sigmoid then
+  // does not wait for the burst of matrix instructions that follows to drain), then the
+  // 2 NT2 layer-2 steps that consume tile t.
+  static __device__ __forceinline__ float forward_stream(const uint32_t* __restrict__ wm, const Feat& f, int lane,
+                                                               const NetOffsets& o) {
     const int h = lane >> 5;
     const float4* b1 = reinterpret_cast<const float4*>(wm + o.b1);
     const float4* b2 = reinterpret_cast<const float4*>(wm + o.b2);
     const uint4* w1 = reinterpret_cast<const uint4*>(wm + o.w1);
     const uint4* w2 = reinterpret_cast<const uint4*>(wm + o.w2);
     const float4* wo = reinterpret_cast<const float4*>(wm + o.wo);
-    floatx16 a1A[NT1], a1B[NT1];
+    floatx16 a2[NT2];
 #pragma unroll
-    for (int t = 0; t < NT1; ++t) { init_bias(b1, t, h, a1A[t]); init_bias(b1, t, h, a1B[t]); }
-    {
-      A4 a_next = load_a(w1, lane, NT1 * KB1 * 64);
+    for (int u = 0; u < NT2; ++u) init_bias(b2, u, h, a2[u]);
+    floatx16 a1;
+    B4 hb[NPL][2];
+    init_bias(b1, 0, h, a1);
 #pragma unroll
-      for (int kb = 0; kb < KB1; ++kb)
+    for (int kb = 0; kb < KB1; ++kb) a1 = mma(load_w1(w1, 0, kb, lane), f.x[0][kb], f.x[NPL - 1][kb], a1);
 #pragma unroll
-        for (int t = 0; t < NT1; ++t) {
-          const A4 a = a_next;
-          const int tn = t + 1 < NT1 ? t + 1 : 0, kn = tn ? kb : kb + 1;
-          if (kn < KB1) a_next = load_a(w1, (tn * KB1 + kn) * 64 + lane, NT1 * KB1 * 64);
-          a1A[t] = mma(a, fA.x[0][kb], fA.x[0][kb], a1A[t]);
-          a1B[t] = mma(a, fB.x[0][kb], fB.x[0][kb], a1B[t]);
-        }
+    for (int t = 0; t < NT1; ++t) {
+      sigmoid16(a1);
+      pack_tile(a1, hb);
+      if (t + 1 < NT1) {
+        init_bias(b1, t + 1, h, a1);
+#pragma unroll
+        for (int kb = 0; kb < KB1; ++kb) a1 = mma(load_w1(w1, t + 1, kb, lane), f.x[0][kb], f.x[NPL - 1][kb], a1);
+      }
+#pragma unroll
+      for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int u = 0; u < NT2; ++u) a2[u] = mma(load_w2(w2, t, b, u, lane), hb[0][b], hb[NPL - 1][b], a2[u]);
     }
-    B4 hbA[NT1][2], hbB[NT1][2];
-    // The vector work of one 32-unit tile as a numbered sequence of instructions, so that it
-    // can be dealt out between matrix instructions: sigmoid + repacking (56 operations) ...
-    auto act_op = [&](int k, floatx16& a, B4 (&hb)[2]) {
-      if (k < 16) a[k] = __builtin_amdgcn_exp2f(a[k]);
-      else if (k < 32) a[k - 16] = 1.0f + a[k - 16];
-      else if (k < 48) a[k - 32] = __builtin_amdgcn_rcpf(a[k - 32]);
-      else {
-        const int p = k - 48;                       // registers 2 p, 2 p + 1 -> word p % 4 of block p / 4
-        uint32_t hi, lo;
-        pack_pair<T, NPL>(a[2 * p], a[2 * p + 1], hi, lo);
-        hb[p / 4].w[p % 4] = hi;
-      }
-    };
-    // ... and sigmoid + output layer (64 operations; q = the tile's 16 output weights)
-    auto fin_op = [&](int k, floatx16& a, const float4 (&q)[4], float& part) {
-      if (k < 16) a[k] = __builtin_amdgcn_exp2f(a[k]);
-      else if (k < 32) a[k - 16] = 1.0f + a[k - 16];
-      else if (k < 48) a[k - 32] = __builtin_amdgcn_rcpf(a[k - 32]);
-      else {
-        const int v = k - 48, g = v / 4, j = v % 4;
-        const float wv = j == 0 ? q[g].x : (j == 1 ? q[g].y : (j == 2 ? q[g].z : q[g].w));
-        part = fmaf(wv, a[v], part);
-      }
-    };
-    constexpr int kStepsT = 2 * NT2;                 // layer-2 matrix instructions per 32-unit input tile
-    constexpr int kSteps = NT1 * kStepsT;            // ... of a whole configuration tile
-    constexpr int kVA = (56 + kStepsT - 1) / kStepsT;
-    constexpr int kVF = (NT2 * 64 + kSteps - 1) / kSteps;
-    const int plane = NT2 * 2 * NT1 * 64;
-    auto w2_index = [&](int step) {                   // step = (t * 2 + b) * NT2 + u
-      const int u = step % NT2, tb = step / NT2;
-      return (u * 2 * NT1 + tb) * 64 + lane;
-    };
-
-    // tile A: sigmoid of layer 1 (nothing to run beside it yet)
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int t = 0; t < NT1; ++t)
-#pragma unroll
-      for (int k = 0; k < 56; ++k) act_op(k, a1A[t], hbA[t]);
-    __builtin_amdgcn_sched_barrier(0);
-
-    // layer 2 of tile A beside the sigmoid of tile B's layer 1
-    floatx16 a2A[NT2], a2B[NT2];
-#pragma unroll
-    for (int u = 0; u < NT2; ++u) init_bias(b2, u, h, a2A[u]);
-    {
-      A4 w_cur = load_a(w2, w2_index(0), plane), w_nxt = load_a(w2, w2_index(1), plane);
-#pragma unroll
-      for (int st = 0; st < kSteps; ++st) {
-        const A4 a = w_cur;
-        w_cur = w_nxt;
-        if (st + 2 < kSteps) w_nxt = load_a(w2, w2_index(st + 2), plane);
-        const int t = st / kStepsT, b = (st / NT2) % 2, u = st % NT2;
-        a2A[u] = mma(a, hbA[t][b], hbA[t][b], a2A[u]);
-        const int i = st % kStepsT;                  // this step's share of tile t's 56 operations
-#pragma unroll
-        for (int k = i * kVA; k < (i + 1) * kVA; ++k)
-          if (k < 56) act_op(k, a1B[t], hbB[t]);
-        __builtin_amdgcn_sched_barrier(0);
-      }
-    }
-
-    // layer 2 of tile B beside tile A's last sigmoid and output layer
-#pragma unroll
-    for (int u = 0; u < NT2; ++u) init_bias(b2, u, h, a2B[u]);
-    float partA = 0.0f;
-    {
-      A4 w_cur = load_a(w2, w2_index(0), plane), w_nxt = load_a(w2, w2_index(1), plane);
-      float4 q[4];
-#pragma unroll
-      for (int st = 0; st < kSteps; ++st) {
-        const A4 a = w_cur;
-        w_cur = w_nxt;
-        if (st + 2 < kSteps) w_nxt = load_a(w2, w2_index(st + 2), plane);
-        const int t = st / kStepsT, b = (st / NT2) % 2, u = st % NT2;
-        a2B[u] = mma(a, hbB[t][b], hbB[t][b], a2B[u]);
-#pragma unroll
-        for (int k = st * kVF; k < (st + 1) * kVF; ++k) {
-          if (k < NT2 * 64) {
-            const int uu = k / 64, kk = k % 64;
-            if (kk == 0) {
-#pragma unroll
-              for (int g = 0; g < 4; ++g) q[g] = wo[(uu * 4 + g) * 2 + h];
-            }
-            fin_op(kk, a2A[uu], q, partA);
-          }
-        }
-        __builtin_amdgcn_sched_barrier(0);
-      }
-    }
-    yA = partA;
-
-    // tile B: last sigmoid and output layer
-    float partB = 0.0f;
+    float part = 0.0f;
 #pragma unroll
     for (int u = 0; u < NT2; ++u) {
       float4 q[4];
 #pragma unroll
       for (int g = 0; g < 4; ++g) q[g] = wo[(u * 4 + g) * 2 + h];
-      __builtin_amdgcn_sched_barrier(0);
-      sigmoid16(a2B[u]);
-      __builtin_amdgcn_sched_barrier(0);
+      sigmoid16(a2[u]);
 #pragma unroll
-      for (int k = 48; k < 64; ++k) fin_op(k, a2B[u], q, partB);
+      for (int g = 0; g < 4; ++g) {
+        part = fmaf(q[g].x, a2[u][4 * g + 0], part);
+        part = fmaf(q[g].y, a2[u][4 * g + 1], part);
+        part = fmaf(q[g].z, a2[u][4 * g + 2], part);
+        part = fmaf(q[g].w, a2[u][4 * g + 3], part);
+      }
     }
-    yB = partB;
+    return part;
   }
 };
 

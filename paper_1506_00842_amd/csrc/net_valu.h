@@ -21,7 +21,6 @@ struct ValuNet {
 
   static constexpr bool kBiasInput = false;
   static constexpr bool kHoist = false;
-  static constexpr bool kPair = false;
   static __device__ __forceinline__ void load_features(const DevSpace& sp, uint32_t i, int lane, bool pow2,
                                                        const NetOffsets&, Feat& f) {
     if (pow2) {

@@ -12,7 +12,6 @@
 //   struct Feat                                   per-tile network input registers
 //   static void load_features(sp, index, lane, pow2, offsets, Feat&)
 //   static void zero_features(Feat&)
-//   static constexpr bool kPair                   forward2() evaluates two tiles of a wave together
 //   static float forward(const uint32_t* member_lds, const Feat&, int lane, const NetOffsets&)
 //        -> the lane's share of the member's output (both halves of a lane pair
 //           (lane, lane ^ 32) are summed by the caller)
@@ -242,22 +241,9 @@ __global__ void __launch_bounds__(NW * 64) sweep_kernel(const SweepParams prm) {
       nm = nm < prm.members_per_stage ? nm : prm.members_per_stage;
       for (int m = 0; m < nm; ++m) {
         const uint32_t* w = stage + (size_t)m * prm.member_words;
-        bool paired[R] = {};
-        if constexpr (Net::kPair && R % 2 == 0) {
-#pragma unroll
-          for (int r = 0; r < R; r += 2) {
-            if (any[r] && any[r + 1]) {      // two tiles of the wave at once
-              float y0, y1;
-              Net::forward2(w, feat[r], feat[r + 1], lane, prm.off, y0, y1);
-              ysum[r] += y0;
-              ysum[r + 1] += y1;
-              paired[r] = paired[r + 1] = true;
-            }
-          }
-        }
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-          if (any[r] && !paired[r]) {
+          if (any[r]) {
             if constexpr (Net::kHoist) ysum[r] += Net::forward(w, feat[r], lane, prm.off, hoist_xs + r * 32, hoist_zs);
             else ysum[r] += Net::forward(w, feat[r], lane, prm.off);
           }

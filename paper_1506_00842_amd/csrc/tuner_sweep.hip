@@ -710,7 +710,9 @@ static int plan_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begi
   P.n_chunks = (uint32_t)n_chunks64;   // count <= 2^32, iter >= 256
   // queue unit: up to kMaxSuper chunks, while every workgroup still gets >= 8 units
   uint32_t super = 1;
-  while (super < (uint32_t)kMaxSuper && n_chunks64 / (2 * super) >= 8ull * max_groups) super *= 2;
+  while (super < (uint32_t)kMaxSuper && 2 * super * (uint32_t)iter <= (uint32_t)(kMaxIter * kMaxSuper) &&
+         n_chunks64 / (2 * super) >= 8ull * max_groups)
+    super *= 2;
   // a resident ensemble keeps its candidate pool (2 k keys + one queue unit) in LDS too if
   // it fits; a smaller unit is worth that
   if (mode == MODE_TOPK && k > 0) {

@@ -220,33 +220,33 @@ def test_other_nets_benchmark_workloads(net):
         say(f"  {net} {w.name}: worst {worst:.3f} x tol({tol:g}), top-{w.k} ok")
 
 
-# The widest one-plane networks (128-wide, bf16) evaluate the two tiles a wave owns in a
-# chunk together (the vector work of one tile between the matrix instructions of the
-# other) whenever both tiles hold a valid configuration; that needs chunks of two tiles
-# per wave, which the library uses for every call of 2^20 configurations or more and for
-# shorter ones whose chunk count suits (tuner_sweep_plan tells).  Below, the same range is
-# swept in one call (two tiles per wave) and in calls of 2^13 (one tile per wave): parity
-# with the oracle at the bf16 tolerance, and the same bits both ways.
+# The 128-wide bf16 network runs with 16 waves per workgroup and two tiles per wave in a chunk
+# (1024 configurations); short calls use one tile per wave.  The same range is swept in one
+# call and in calls of 2^13 configurations: parity with the oracle at the bf16 tolerance, and
+# the same bits both ways (what a configuration's prediction is does not depend on how a
+# sweep is cut into calls or on the chunk shape).
 WIDE_BF16_RANGES = [
     # (begin, count): parameter 2 has stride 2^18 and parameter 3 stride 2^15 in this space,
     # and a configuration is valid iff digit 2 <= digit 3 (and digit 0 + digit 1 <= 10): a
     # range of 2^18 from a block with digit 2 = 3 has three invalid and five valid blocks of
     # 2^15, each a run of wholly invalid or wholly valid chunks
     ((3 << 18) + 4321, (1 << 18) - 5),
-    # a long range (work queue and live-chunk list) across a change of digit 1 with
-    # digit 0 + digit 1 = 10 -> 11 (valid -> all invalid), ragged at both ends
-    ((3 << 24) + (7 << 21) + (5 << 18) + 31, (1 << 20) + 777),
+    # a long range (work queue and live-chunk list, full chunks) across a change of digit 1
+    # with digit 0 + digit 1 = 10 -> 11 (valid -> all invalid), ragged at both ends
+    ((3 << 24) + (7 << 21) + (2 << 18) + 31, (1 << 21) + 777),
 ]
 
 
 @pytest.mark.parametrize("begin,count", WIDE_BF16_RANGES)
-def test_wide_bf16_two_tiles_per_wave_against_oracle_and_one_tile_path(begin, count):
+def test_wide_bf16_long_ranges_against_oracle_and_short_calls(begin, count):
     import paper_1506_00842_amd as T
     w = wl.wide()
     sw = sweep_for(w, precision=T.TUNER_BF16_MFMA)
     plan = T.tuner_sweep_plan(sw.space, sw.model, begin, count, 0)
-    assert plan["tiles_per_wave"] == plan["variant_tiles_per_wave"] == 2, plan
     say("wide bf16", begin, count, plan)
+    assert plan["waves"] == 16 and plan["variant_tiles_per_wave"] == 2
+    if count >= 1 << 21:
+        assert plan["tiles_per_wave"] == 2 and plan["dynamic_queue"] == 1 and plan["live_chunk_list"] == 1
     pred, mask = sw.predict_all(begin, count)
     torch.cuda.synchronize()
     oy, ov, _ = oracle.predict_range(w.space, w.model, begin, count, threads=THREADS)
@@ -254,7 +254,7 @@ def test_wide_bf16_two_tiles_per_wave_against_oracle_and_one_tile_path(begin, co
     assert 0.15 < ov.mean() < 0.85                     # both kinds of chunks are in the range
     worst, rel = parity.check_predictions(pred.cpu().numpy(), oy, ov, tol=TOL_BF16)
     say(f"  one call: worst {worst:.3f} x tol(1e-2), pure-relative worst {rel:.2e}")
-    # the same range in pieces of 2^13 configurations: one tile per wave, plain forward()
+    # the same range in pieces of 2^13 configurations: one tile per wave
     piece = 1 << 13
     assert T.tuner_sweep_plan(sw.space, sw.model, begin, piece, 0)["tiles_per_wave"] == 1
     pred2 = torch.empty_like(pred)
@@ -264,7 +264,7 @@ def test_wide_bf16_two_tiles_per_wave_against_oracle_and_one_tile_path(begin, co
         sw.predict_all(begin + t0, c, out=pred2[t0:t0 + c], mask=mask2[t0:t0 + c])
     torch.cuda.synchronize()
     assert torch.equal(mask, mask2)
-    assert torch.equal(pred.view(torch.int32), pred2.view(torch.int32)), "two-tile and one-tile paths differ in bits"
+    assert torch.equal(pred.view(torch.int32), pred2.view(torch.int32)), "long and short calls differ in bits"
     # top-k: one call against the running result over the pieces (bit-identical), and the
     # band rule against the oracle at the bf16 tolerance
     sw.topk(begin, count)

@@ -211,12 +211,13 @@ def test_sweep_plan_of_the_benchmark_configurations():
     p = plan(ww, 0, 1 << 27, 1000)
     assert p["layer1"] == 1 and p["waves"] == 8 and p["members_per_stage"] == 1 and p["n_stages"] == 16
     assert p["double_buffer"] == 1 and p["pool_in_lds"] == 0
-    # bf16, 128 wide: two tiles per wave for calls of 2^20 configurations or more; shorter
-    # calls take whichever of one or two gives fewer rounds of chunks over the 256 workgroups
-    for count, r in ((1 << 27, 2), ((1 << 20) + 777, 2), ((1 << 18) - 5, 2), ((1 << 18) + 777, 1),
-                     (1 << 14, 1), (1 << 13, 1), (12007, 1)):
+    # bf16, 128 wide: 16 waves per workgroup, chunks of 1024 configurations (two tiles per wave)
+    # for calls of 2^21 configurations or more; shorter calls take whichever of one or two
+    # tiles per wave gives fewer rounds of chunks over the 256 workgroups
+    for count, r in ((1 << 27, 2), ((1 << 21) + 777, 2), ((1 << 18) - 5, 2), ((1 << 18) + 777, 1), (1 << 14, 1), (1 << 13, 1), (12007, 1)):
         p = plan(ww, 0 if count == 1 << 27 else 3 << 18, count, 0, precision=T.TUNER_BF16_MFMA)
-        assert p["network"] == 1 and p["variant_tiles_per_wave"] == 2 and p["tiles_per_wave"] == r, (count, p)
+        assert p["network"] == 1 and p["waves"] == 16 and p["variant_tiles_per_wave"] == 2, (count, p)
+        assert p["tiles_per_wave"] == r, (count, p)
     assert p["members_per_stage"] == 2 and p["double_buffer"] == 1
     # the streamed space: chunks of 2^28, two members per stage
     ws = wl.streamed()
