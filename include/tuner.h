@@ -233,6 +233,38 @@ int tuner_predict_topk(const tuner_space* space, const tuner_model* model,
                        size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Sweeps of one model over one space, call after call (the chunks of a streamed
+ * space, the repeated sweeps of a tuning session): what every call would derive
+ * again from the same inputs is made once.  tuner_prepare writes the sweep's
+ * header, the space's decoder tables (Section 5.1) and the ensemble's weights in
+ * the operand order of the kernels (Section 5.2) into the workspace;
+ * tuner_predict_topk_prepared and tuner_predict_all_prepared are
+ * tuner_predict_topk and tuner_predict_all without that step (one kernel fewer
+ * per call; the same results, bit for bit).
+ *   - The workspace must be the one tuner_prepare wrote, for the same space and
+ *     model (same widths, precision, algo and weights), of at least
+ *     tuner_workspace_bytes(space, model, k) bytes for the largest k used.
+ *   - Between prepared calls its contents must be left alone; calls are ordered
+ *     on one stream.  tuner_predict_topk, tuner_predict_all and
+ *     tuner_predict_indices on the same workspace write their own preparation
+ *     over it: prepare again after them, after a failed call, and whenever the
+ *     weights change.
+ *   - model->weights_dev is not read by the prepared calls.
+ * Errors as for the calls they replace.
+ */
+int tuner_prepare(const tuner_space* space, const tuner_model* model, void* workspace_dev,
+                  size_t workspace_bytes, void* hip_stream);
+int tuner_predict_topk_prepared(const tuner_space* space, const tuner_model* model,
+                                uint64_t index_begin, uint64_t index_count, int32_t k,
+                                int32_t merge_with_existing, float* topk_values_dev,
+                                uint32_t* topk_indices_dev, int32_t* n_found_dev,
+                                void* workspace_dev, size_t workspace_bytes, void* hip_stream);
+int tuner_predict_all_prepared(const tuner_space* space, const tuner_model* model,
+                               uint64_t index_begin, uint64_t index_count, float* predictions_dev,
+                               uint8_t* valid_mask_dev, void* workspace_dev, size_t workspace_bytes,
+                               void* hip_stream);
+
+/*
  * tuner_predict_topk for callers that cannot allocate device memory or bring a
  * workspace: code under HIP graph capture, tight serving loops, harnesses that
  * forbid hipMalloc.  Same arguments, results and errors as tuner_predict_topk

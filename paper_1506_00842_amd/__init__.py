@@ -32,7 +32,8 @@ EXPORTS = [
     "tuner_version", "tuner_profile_enable", "tuner_profile_read", "tuner_profile_read_train", "tuner_hoisted_parameters", "tuner_tabulated_parameters",
     "tuner_predict_indices", "tuner_sample_workspace_bytes", "tuner_sample_valid",
     "tuner_train_workspace_bytes", "tuner_train_ensemble", "tuner_mean_relative_error",
-    "tuner_best_of", "tuner_predict_topk_static", "tuner_sweep_plan", "tuner_profile_pending",
+    "tuner_best_of", "tuner_predict_topk_static", "tuner_sweep_plan", "tuner_profile_pending", "tuner_prepare",
+    "tuner_predict_topk_prepared", "tuner_predict_all_prepared",
 ]
 
 
@@ -105,6 +106,9 @@ def load_library():
                                             C.c_void_p]
     L.tuner_predict_all.argtypes = [C.c_void_p, C.POINTER(_Model), C.c_uint64, C.c_uint64,
                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    L.tuner_prepare.argtypes = [C.c_void_p, C.POINTER(_Model), C.c_void_p, C.c_size_t, C.c_void_p]
+    L.tuner_predict_topk_prepared.argtypes = L.tuner_predict_topk.argtypes
+    L.tuner_predict_all_prepared.argtypes = L.tuner_predict_all.argtypes
     L.tuner_decode_range.argtypes = [C.c_void_p, C.c_uint64, C.c_uint64, C.c_void_p, C.c_void_p,
                                      C.c_void_p, C.c_void_p]
     L.tuner_predict_indices.argtypes = [C.c_void_p, C.POINTER(_Model), C.c_uint64, C.c_void_p,
@@ -287,6 +291,26 @@ def tuner_predict_topk_static(space, model, index_begin, index_count, k, merge_w
         space.ptr, C.byref(model.c), int(index_begin), int(index_count), int(k),
         int(merge_with_existing), _dp(topk_values_dev), _dp(topk_indices_dev), _dp(n_found_dev),
         _stream(stream)))
+
+
+def tuner_prepare(space, model, workspace_dev, stream=None):
+    _check(load_library().tuner_prepare(space.ptr, C.byref(model.c), _dp(workspace_dev), _nbytes(workspace_dev),
+                                        _stream(stream)))
+
+
+def tuner_predict_topk_prepared(space, model, index_begin, index_count, k, merge_with_existing,
+                                topk_values_dev, topk_indices_dev, n_found_dev, workspace_dev, stream=None):
+    _check(load_library().tuner_predict_topk_prepared(
+        space.ptr, C.byref(model.c), int(index_begin), int(index_count), int(k),
+        int(merge_with_existing), _dp(topk_values_dev), _dp(topk_indices_dev), _dp(n_found_dev),
+        _dp(workspace_dev), _nbytes(workspace_dev), _stream(stream)))
+
+
+def tuner_predict_all_prepared(space, model, index_begin, index_count, predictions_dev, valid_mask_dev,
+                               workspace_dev, stream=None):
+    _check(load_library().tuner_predict_all_prepared(
+        space.ptr, C.byref(model.c), int(index_begin), int(index_count), _dp(predictions_dev),
+        _dp(valid_mask_dev), _dp(workspace_dev), _nbytes(workspace_dev), _stream(stream)))
 
 
 def tuner_predict_all(space, model, index_begin, index_count, predictions_dev, valid_mask_dev,

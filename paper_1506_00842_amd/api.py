@@ -7,7 +7,8 @@ import torch
 
 from . import (ModelHandle, TUNER_ALGO_AUTO, TUNER_FP32, tuner_best_of, tuner_decode_range,
                tuner_mean_relative_error, tuner_predict_all, tuner_predict_indices,
-               tuner_predict_topk, tuner_sample_valid, tuner_sample_workspace_bytes,
+               tuner_predict_topk, tuner_predict_topk_prepared, tuner_predict_all_prepared, tuner_prepare,
+               tuner_sample_valid, tuner_sample_workspace_bytes,
                tuner_space_create, tuner_space_size, tuner_train_ensemble,
                tuner_train_workspace_bytes, tuner_workspace_bytes)
 
@@ -31,17 +32,25 @@ class Sweep:
         self.k = int(k)
         nbytes = tuner_workspace_bytes(self.space, self.model, self.k)
         self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        self.prepared = False
         if self.k > 0:
             self.values = torch.empty(self.k, dtype=torch.float32, device=self.device)
             # uint32 payload kept in an int32 tensor (same bytes)
             self.indices = torch.empty(self.k, dtype=torch.int32, device=self.device)
             self.n_found = torch.zeros(1, dtype=torch.int32, device=self.device)
 
+    def prepare(self, stream=None):
+        """Packs tables and weights into the workspace once; topk() and predict_all() then use
+        the prepared entry points until a call that repacks (predict_indices) is made."""
+        tuner_prepare(self.space, self.model, self.workspace, stream)
+        self.prepared = True
+
     def topk(self, begin: int = 0, count: int | None = None, merge: bool = False, stream=None):
         """Enqueues one call; results stay on the device (self.values, self.indices, self.n_found)."""
         count = self.n_configs - begin if count is None else count
-        tuner_predict_topk(self.space, self.model, begin, count, self.k, 1 if merge else 0,
-                           self.values, self.indices, self.n_found, self.workspace, stream)
+        fn = tuner_predict_topk_prepared if self.prepared else tuner_predict_topk
+        fn(self.space, self.model, begin, count, self.k, 1 if merge else 0,
+           self.values, self.indices, self.n_found, self.workspace, stream)
 
     def topk_host(self):
         """Copies the current result to the host: (values f32[n], indices u64[n])."""
@@ -57,8 +66,8 @@ class Sweep:
             out = torch.empty(count, dtype=torch.float32, device=self.device)
         if want_mask and mask is None:
             mask = torch.empty(count, dtype=torch.uint8, device=self.device)
-        tuner_predict_all(self.space, self.model, begin, count, out, mask if want_mask else None,
-                          self.workspace, stream)
+        fn = tuner_predict_all_prepared if self.prepared else tuner_predict_all
+        fn(self.space, self.model, begin, count, out, mask if want_mask else None, self.workspace, stream)
         return out, mask
 
     def decode(self, begin: int, count: int):
@@ -74,6 +83,7 @@ class Sweep:
         out = torch.empty(n, dtype=torch.float32, device=self.device)
         mask = torch.empty(n, dtype=torch.uint8, device=self.device) if want_mask else None
         tuner_predict_indices(self.space, self.model, n, indices, out, mask, self.workspace, stream)
+        self.prepared = False          # the list evaluation packs the weights in its own layout
         return out, mask
 
 

@@ -30,7 +30,9 @@ struct WsHeader {
   uint32_t work_counter;      // next chunk of the dynamic queue
   float bo_sum;               // sum of the members' output biases
   uint32_t n_live;            // entries of the live-chunk list (long constrained ranges)
-  uint32_t pad[11];
+  uint32_t done;              // workgroups of the running sweep that have finished; the last one
+                              // puts tau, work_counter, n_live and done back to their idle values
+  uint32_t pad[10];
 };
 
 // Model shape and the layout of one packed member, in 32-bit words.
@@ -59,6 +61,7 @@ struct SweepParams {
   int32_t r_used;              // tiles per wave and chunk actually used (1 .. the variant's R)
   int32_t n_members, members_per_stage, n_stages, member_words;
   int32_t mode, k;
+  int32_t merge;              // top-k: the caller's outputs hold a running result (values, indices, n_found)
   float inv_members;          // 1 / n_members, rounded once from double
   uint32_t cap, kp;           // pool capacity per workgroup, k rounded up to a power of two
   uint32_t lds_entries;       // keys that fit the LDS region after the space tables (weights / sort scratch)
@@ -76,6 +79,10 @@ struct SweepParams {
   const uint32_t* index_list;  // optional: configuration t of the "range" is index_list[t]
   WsHeader* hdr;
   unsigned long long* pools;
+  unsigned long long* extra;   // top-k: kp keys, the running result as a sorted key list (written by the sweep)
+  const float* run_values;     // the caller's top-k outputs, read when merge is set
+  const uint32_t* run_indices;
+  const int32_t* run_found;
   float* pred;
   uint8_t* mask;
 };

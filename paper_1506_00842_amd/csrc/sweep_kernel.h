@@ -54,6 +54,20 @@ __global__ void __launch_bounds__(NW * 64) sweep_kernel(const SweepParams prm) {
     for (int x = tid; x < (int)(sizeof(DevSpace) / 4); x += kThreads) dst[x] = src[x];
   }
   if (tid == 0) { s_cnt = 0; s_tau_local = kKeyMax; s_compact = 0; }
+  if (prm.mode == MODE_TOPK) {
+    // The running result of earlier calls becomes one more sorted key list for the merge
+    // that follows this kernel (every workgroup converts a slice), and its k-th key, if it
+    // has k entries, is an upper bound of the final k-th key from the start.
+    int found = 0;
+    if (prm.merge) {
+      found = *prm.run_found;
+      found = found < 0 ? 0 : (found > prm.k ? prm.k : found);
+    }
+    for (uint32_t x = blockIdx.x * kThreads + tid; x < prm.kp; x += gridDim.x * kThreads)
+      prm.extra[x] = ((int)x < found) ? make_key(prm.run_values[x], prm.run_indices[x]) : kKeyMax;
+    if (tid == 0 && found == prm.k && found > 0)
+      s_tau_local = make_key(prm.run_values[prm.k - 1], prm.run_indices[prm.k - 1]);
+  }
   auto load_stage = [&](int st) {
     const int first = st * prm.members_per_stage;
     int nm = prm.n_members - first;
@@ -159,9 +173,12 @@ __global__ void __launch_bounds__(NW * 64) sweep_kernel(const SweepParams prm) {
       if (tid == 0) {
         if (n >= (uint32_t)prm.k) {
           const unsigned long long t = pool_in_lds ? lpool[prm.k - 1] : gpool[prm.k - 1];
-          s_tau_local = t;
-          atomicMin(&prm.hdr->tau, t);
+          if (t < s_tau_local) s_tau_local = t;
+          // (the returned value is used, so the atomic has completed before this workgroup
+          // reports itself done at the end of the kernel)
+          const unsigned long long before = atomicMin(&prm.hdr->tau, t);
           if (t < s_tau) s_tau = t;
+          if (before < s_tau) s_tau = before;
           s_cnt = prm.k;
         }
       }
@@ -299,6 +316,18 @@ __global__ void __launch_bounds__(NW * 64) sweep_kernel(const SweepParams prm) {
       for (uint32_t x = n + tid; x < n2; x += kThreads) gpool[x] = kKeyMax;
       __syncthreads();
       sort_pool(gpool, n2, lds_keys, lds_entries, tid, kThreads);
+    }
+  }
+  // The last workgroup to finish leaves the header as the next call expects it (every other
+  // workgroup's accesses to these words have completed: their results were consumed before
+  // the increment below), so that a call on a prepared workspace needs no reset kernel.
+  if (tid == 0) {
+    const uint32_t finished = atomicAdd(&prm.hdr->done, 1u);
+    if (finished == gridDim.x - 1) {
+      prm.hdr->work_counter = 0u;
+      prm.hdr->n_live = 0u;
+      prm.hdr->tau = kKeyMax;
+      prm.hdr->done = 0u;
     }
   }
 }

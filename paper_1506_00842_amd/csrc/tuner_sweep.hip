@@ -45,12 +45,6 @@ struct PrepParams {
   uint32_t* packed;
   DevSpace* space_out;
   WsHeader* hdr;
-  unsigned long long* extra;  // key list of the running result
-  uint32_t kp;
-  int32_t k, merge;
-  const float* in_values;
-  const uint32_t* in_indices;
-  const int32_t* in_found;
 };
 
 __global__ void __launch_bounds__(256) prep_kernel(const DevSpace sp, const PrepParams pp) {
@@ -83,16 +77,7 @@ __global__ void __launch_bounds__(256) prep_kernel(const DevSpace sp, const Prep
       if (gtid == word % gsize) pp.space_out->pa[sh.P].lut_off4 = 4u * (uint32_t)kLutOne;
     }
   }
-  // running result -> key list
-  int found = 0;
-  if (pp.merge) {
-    found = *pp.in_found;
-    found = found < 0 ? 0 : (found > pp.k ? pp.k : found);
-  }
-  if (pp.extra) {
-    for (uint32_t x = gtid; x < pp.kp; x += gsize)
-      pp.extra[x] = ((int)x < found) ? make_key(pp.in_values[x], pp.in_indices[x]) : kKeyMax;
-  }
+  // header: the idle state every sweep starts from and its last workgroup restores
   if (gtid == 0) {
     const int r_bo = sh.raw_member_floats - 1;
     float bo = 0.0f;
@@ -100,9 +85,19 @@ __global__ void __launch_bounds__(256) prep_kernel(const DevSpace sp, const Prep
     pp.hdr->bo_sum = bo;
     pp.hdr->work_counter = 0u;
     pp.hdr->n_live = 0u;
-    pp.hdr->tau = (pp.merge && found == pp.k && pp.k > 0)
-                      ? make_key(pp.in_values[pp.k - 1], pp.in_indices[pp.k - 1]) : kKeyMax;
+    pp.hdr->done = 0u;
+    pp.hdr->tau = kKeyMax;
   }
+}
+
+// The result of a top-k call over an empty range that merges with nothing: no configuration.
+__global__ void __launch_bounds__(256)
+empty_result_kernel(int32_t k, float* values, uint32_t* indices, int32_t* n_found) {
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < k; i += gridDim.x * blockDim.x) {
+    values[i] = __builtin_inff();
+    indices[i] = 0xffffffffu;
+  }
+  if (blockIdx.x == 0 && threadIdx.x == 0) *n_found = 0;
 }
 
 // ---------------------------------------------------------------------------
@@ -636,6 +631,21 @@ static int scratch_address(void** out) {
   return TUNER_OK;
 }
 
+static int launch_prep(const tuner_space* sp, const tuner_model* m, const Shape& sh, WsHeader* hdr,
+                       DevSpace* space_dev, uint32_t* packed, hipStream_t stream) {
+  PrepParams pp{};
+  pp.sh = sh;
+  pp.raw = m->weights_dev;
+  pp.packed = packed;
+  pp.space_out = space_dev;
+  pp.hdr = hdr;
+  const uint32_t total_packed = (uint32_t)sh.E * sh.member_words;
+  const unsigned prep_blocks = std::min<unsigned>(1024, (total_packed + 255) / 256);
+  hipLaunchKernelGGL(prep_kernel, dim3(prep_blocks), dim3(256), 0, stream, sp->dev, pp);
+  TUNER_HIP_TRY(hipGetLastError());
+  return TUNER_OK;
+}
+
 // Everything a sweep call decides before it touches the device: the network layout and
 // kernel variant, how the range is cut into chunks and queue units, how the ensemble goes
 // through LDS, where the candidate pool lives, and the launches of the merge that follows.
@@ -797,10 +807,13 @@ static int plan_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begi
   return TUNER_OK;
 }
 
+// prepared: the workspace already holds the header, the space tables and the packed weights
+// of this space and model in the layout of a range sweep (tuner_prepare), so no packing
+// kernel is launched.
 static int run_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin, uint64_t count,
                      int mode, int k, int merge, float* values, uint32_t* indices, int32_t* n_found,
                      float* pred, uint8_t* mask, void* ws, size_t ws_bytes, hipStream_t stream,
-                     const uint32_t* index_list = nullptr) {
+                     const uint32_t* index_list = nullptr, bool prepared = false) {
   // ---- everything that can fail comes before the first launch
   // (argument errors are reported even where there is no device to ask: the plan then uses
   // MI355X's figures and the device error comes after them)
@@ -847,25 +860,20 @@ static int run_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin
   unsigned long long* pools = reinterpret_cast<unsigned long long*>(base + L.o_pools);
   unsigned long long* extra = reinterpret_cast<unsigned long long*>(base + L.o_extra);
 
-  PrepParams pp{};
-  pp.sh = sh;
-  pp.raw = m->weights_dev;
-  pp.packed = packed;
-  pp.space_out = space_dev;
-  pp.hdr = hdr;
-  pp.extra = mode == MODE_TOPK ? extra : nullptr;
-  pp.kp = L.kp;
-  pp.k = k;
-  pp.merge = merge;
-  pp.in_values = values;
-  pp.in_indices = indices;
-  pp.in_found = n_found;
-  const uint32_t total_packed = (uint32_t)sh.E * sh.member_words;
-  const unsigned prep_blocks = std::min<unsigned>(1024, (total_packed + 255) / 256);
-  hipLaunchKernelGGL(prep_kernel, dim3(prep_blocks), dim3(256), 0, stream, sp->dev, pp);
-  TUNER_HIP_TRY(hipGetLastError());
+  if (!prepared) {
+    rc = launch_prep(sp, m, sh, hdr, space_dev, packed, stream);
+    if (rc) return rc;
+  }
 
   const uint32_t groups = P.groups;
+  if (groups == 0 && mode == MODE_TOPK) {
+    // nothing is swept: the running result stays as it is, or there is no result at all
+    if (!merge) {
+      hipLaunchKernelGGL(empty_result_kernel, dim3((k + 255) / 256), dim3(256), 0, stream, k, values, indices, n_found);
+      TUNER_HIP_TRY(hipGetLastError());
+    }
+    return TUNER_OK;
+  }
   if (groups > 0) {
     SweepParams sw{};
     sw.begin = begin;
@@ -881,6 +889,11 @@ static int run_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin
     sw.member_words = sh.member_words;
     sw.off = NetOffsets{sh.o_w1, sh.o_w2, sh.o_b1, sh.o_b2, sh.o_wo, sh.H1, sh.H2, sh.o_wh, sh.p0};
     sw.mode = mode;
+    sw.merge = merge;
+    sw.extra = mode == MODE_TOPK ? extra : nullptr;
+    sw.run_values = values;
+    sw.run_indices = indices;
+    sw.run_found = n_found;
     sw.inv_members = (float)(1.0 / (double)sh.E);
     sw.k = k;
     sw.cap = L.cap;
@@ -1120,6 +1133,52 @@ int tuner_predict_topk(const tuner_space* space, const tuner_model* model, uint6
   return tuner::run_sweep(space, model, index_begin, index_count, tuner::MODE_TOPK, k,
                           merge_with_existing ? 1 : 0, topk_values_dev, topk_indices_dev, n_found_dev,
                           nullptr, nullptr, workspace_dev, workspace_bytes, (hipStream_t)hip_stream);
+}
+
+int tuner_prepare(const tuner_space* space, const tuner_model* model, void* workspace_dev,
+                  size_t workspace_bytes, void* hip_stream) {
+  if (!space || !model) return set_error(TUNER_EINVAL, "null argument");
+  tuner::DeviceInfo di;
+  const int dev_rc = tuner::device_info(&di);
+  const std::string dev_msg = dev_rc ? std::string(tuner_last_error()) : std::string();
+  if (dev_rc) di = tuner::device_info_or_default();
+  tuner::Shape sh{};
+  const tuner::Variant* var = nullptr;
+  int rc = tuner::choose_shape(space, model, true, di.max_lds, &sh, &var);
+  if (rc) return rc;
+  const tuner::Layout L = tuner::make_layout(sh, 0, space->n_configs, var);
+  // header, tables and packed weights come first in the workspace, whatever k a later call uses
+  if (!workspace_dev || workspace_bytes < L.o_pools)
+    return set_error(TUNER_EWORKSPACE, "workspace missing or too small");
+  if ((reinterpret_cast<uintptr_t>(workspace_dev) & 255) != 0)
+    return set_error(TUNER_EWORKSPACE, "workspace not 256-byte aligned");
+  if (dev_rc) return set_error(dev_rc, dev_msg);
+  unsigned char* base = static_cast<unsigned char*>(workspace_dev);
+  return tuner::launch_prep(space, model, sh, reinterpret_cast<tuner::WsHeader*>(base + L.o_hdr),
+                            reinterpret_cast<tuner::DevSpace*>(base + L.o_space),
+                            reinterpret_cast<uint32_t*>(base + L.o_packed), (hipStream_t)hip_stream);
+}
+
+int tuner_predict_topk_prepared(const tuner_space* space, const tuner_model* model, uint64_t index_begin,
+                                uint64_t index_count, int32_t k, int32_t merge_with_existing,
+                                float* topk_values_dev, uint32_t* topk_indices_dev, int32_t* n_found_dev,
+                                void* workspace_dev, size_t workspace_bytes, void* hip_stream) {
+  if (!space || !model || !topk_values_dev || !topk_indices_dev || !n_found_dev)
+    return set_error(TUNER_EINVAL, "null argument");
+  if (k < 1) return set_error(TUNER_EINVAL, "k must be >= 1");
+  if (k > TUNER_MAX_K) return set_error(TUNER_ETOOLARGE, "k > TUNER_MAX_K");
+  return tuner::run_sweep(space, model, index_begin, index_count, tuner::MODE_TOPK, k,
+                          merge_with_existing ? 1 : 0, topk_values_dev, topk_indices_dev, n_found_dev,
+                          nullptr, nullptr, workspace_dev, workspace_bytes, (hipStream_t)hip_stream, nullptr, true);
+}
+
+int tuner_predict_all_prepared(const tuner_space* space, const tuner_model* model, uint64_t index_begin,
+                               uint64_t index_count, float* predictions_dev, uint8_t* valid_mask_dev,
+                               void* workspace_dev, size_t workspace_bytes, void* hip_stream) {
+  if (!space || !model || !predictions_dev) return set_error(TUNER_EINVAL, "null argument");
+  return tuner::run_sweep(space, model, index_begin, index_count, tuner::MODE_ALL, 0, 0, nullptr,
+                          nullptr, nullptr, predictions_dev, valid_mask_dev, workspace_dev,
+                          workspace_bytes, (hipStream_t)hip_stream, nullptr, true);
 }
 
 int tuner_predict_topk_static(const tuner_space* space, const tuner_model* model, uint64_t index_begin,

@@ -499,3 +499,56 @@ def test_profile_events_recorded_and_dropped():
         T.tuner_profile_enable(False)
     assert T.tuner_profile_pending() == 0
     torch.cuda.synchronize()
+
+
+# ------------------------------------------------------- prepared workspace ---
+@pytest.mark.parametrize("maker,kw_name", [(wl.paper_raycasting, "f32"), (wl.conv_shaped, "f32"), (wl.large, "f32"),
+                                           (wl.wide, "bf16"), (wl.paper_stereo, "split16"), (wl.tiny, "valu")])
+def test_prepared_calls_equal_plain_calls(maker, kw_name):
+    """tuner_prepare once, then prepared calls: the same bits as the plain entry points, call
+    after call (the last workgroup of every sweep leaves the header ready for the next one),
+    for short ranges, long ranges with the work queue and the live-chunk list, chunked running
+    results, empty ranges, and predict_all in between."""
+    import paper_1506_00842_amd as T
+    kw = {"f32": {}, "bf16": dict(precision=T.TUNER_BF16_MFMA), "split16": dict(algo=T.TUNER_ALGO_SPLIT16),
+          "valu": dict(algo=T.TUNER_ALGO_VALU)}[kw_name]
+    w = maker()
+    n = w.space.n_configs
+    ref = sweep_for(w, **kw)
+    sw = sweep_for(w, **kw)
+    sw.prepare()
+    long_count = min(n, (1 << 22) + 12345)
+    calls = [(0, min(n, 100003), False), (n // 3, min(n - n // 3, 70001), True), (5, 0, True), (n - min(n, 4099), min(n, 4099), True),
+             (0, long_count, False), (n - long_count, long_count, n > 2 * long_count), (7, 0, False), (0, min(n, 33), False)]
+    for rep in range(2):
+        for begin, count, merge in calls:
+            ref.topk(begin, count, merge=merge)
+            sw.topk(begin, count, merge=merge)
+            torch.cuda.synchronize()
+            assert torch.equal(sw.n_found, ref.n_found), (begin, count, merge)
+            assert torch.equal(sw.values.view(torch.int32), ref.values.view(torch.int32)), (begin, count, merge)
+            assert torch.equal(sw.indices, ref.indices), (begin, count, merge)
+            if count and count <= 100003:
+                p0, m0 = ref.predict_all(begin, count)
+                p1, m1 = sw.predict_all(begin, count)
+                torch.cuda.synchronize()
+                assert torch.equal(p0.view(torch.int32), p1.view(torch.int32)) and torch.equal(m0, m1)
+    p0, m0 = ref.predict_all(n - long_count, long_count)
+    p1, m1 = sw.predict_all(n - long_count, long_count)
+    torch.cuda.synchronize()
+    assert torch.equal(p0.view(torch.int32), p1.view(torch.int32)) and torch.equal(m0, m1)
+    # against the oracle too, on a range the oracle sweeps in a second
+    begin, count = (n // 3, min(n - n // 3, 70001))
+    sw.topk(begin, count)
+    torch.cuda.synchronize()
+    oy, ov, _ = oracle.predict_range(w.space, w.model, begin, count, threads=THREADS)
+    gv, gi = sw.topk_host()
+    parity.check_topk(gv, gi, oy, ov, begin, w.k, tol=TOL_BF16 if kw_name == "bf16" else parity.TOL_FP32)
+    # the list evaluation repacks the weights: the wrapper falls back to plain calls after it
+    idx = torch.arange(begin, begin + 1000, dtype=torch.int32, device=sw.device)
+    sw.predict_indices(idx)
+    assert not sw.prepared
+    sw.topk(begin, count)
+    torch.cuda.synchronize()
+    gv2, gi2 = sw.topk_host()
+    assert np.array_equal(gi, gi2) and np.array_equal(gv, gv2)
