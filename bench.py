@@ -212,6 +212,8 @@ def main():
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (a kernel of known HBM "
                          "traffic, to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
+    ap.add_argument("--prepared", action="store_true",
+                    help="tuner_prepare once before the warm-up, then prepared calls (no packing kernel per call)")
     ap.add_argument("--no-other-workloads", action="store_true",
                     help="skip the short runs of the other benchmark configurations (default workload only)")
     args = ap.parse_args()
@@ -233,6 +235,8 @@ def main():
     chunk = w.chunk if w.chunk else N
     sw = Sweep(sp, m, w.k if args.mode == "topk" else 0, **net_kwargs(T, args.net))
     stream = torch.cuda.current_stream()
+    if args.prepared:
+        sw.prepare(stream)
     pred = None
     if args.mode == "all":
         pred = torch.empty(chunk, dtype=torch.float32, device=sw.device)
@@ -307,7 +311,7 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if args.net == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": w.name, "n_configs": N, "n_valid": n_valid, "k": w.k,
                    "members": m.n_members, "widths": list(m.widths), "mode": args.mode,
-                   "chunk": chunk, "net": args.net, "hip_graph": bool(args.graph)},
+                   "chunk": chunk, "net": args.net, "hip_graph": bool(args.graph), "prepared": bool(args.prepared)},
         "roofline": roof,
     }
     if args.mode == "all":
@@ -421,16 +425,18 @@ def other_workloads(T, torch, wl, Sweep, stream):
     space, a few steps each, outside the timed region of the headline."""
     res = {}
 
-    def leg(name, w, net, mode, steps, warmup):
+    def leg(name, w, net, mode, steps, warmup, prepared=False):
         N = w.space.n_configs
         chunk = w.chunk if w.chunk else N
         sw = Sweep(w.space, w.model, w.k if mode == "topk" else 0, **net_kwargs(T, net))
+        if prepared:
+            sw.prepare(stream)
         pred = torch.empty(chunk, dtype=torch.float32, device=sw.device) if mode == "all" else None
         r = time_steps(T, torch, make_step(sw, N, chunk, mode, pred, stream), steps, warmup)
         ms = r["ms_per_step_no_events"] if r["ms_per_step"] < 1.0 else r["ms_per_step"]
         e = {"workload": w.name, "net": net, "mode": mode, "k": w.k if mode == "topk" else 0,
              "ms_per_step": ms, "configs_per_s": N / (ms * 1e-3), "sweep_kernel_ms": r["kernel_ms"],
-             "launches_per_step": r["launches_per_step"], "steps": steps}
+             "launches_per_step": r["launches_per_step"], "steps": steps, "prepared": prepared}
         roof = roofline_of(T, sw, w, net, r["kernel_ms"], r["launches_per_step"])
         if roof is not None and ms >= 1.0:
             e["frac_of_peak"] = roof["frac"]
@@ -444,10 +450,13 @@ def other_workloads(T, torch, wl, Sweep, stream):
     leg("cfg4-f32", wl.wide(), "f32-mfma", "topk", 3, 1)
     leg("cfg4-bf16", wl.wide(), "bf16", "topk", 5, 1)
     leg("cfg5-streamed-16-chunks", wl.streamed(), "f32-mfma", "topk", 2, 1)
-    # short sweeps: latency per call (no roofline fraction: they are bound by fixed costs)
-    leg("cfg1-tiny", wl.tiny(), "f32-mfma", "topk", 200, 20)
-    leg("cfg2-conv-shaped", wl.conv_shaped(), "f32-mfma", "topk", 200, 20)
-    leg("paper-convolution", wl.paper_convolution(), "f32-mfma", "topk", 200, 20)
+    # short sweeps: latency per call (no roofline fraction: they are bound by fixed costs), with
+    # the packing kernel in every call and with the workspace prepared once
+    for prepared in (False, True):
+        tag = "-prepared" if prepared else ""
+        leg("cfg1-tiny" + tag, wl.tiny(), "f32-mfma", "topk", 200, 20, prepared)
+        leg("cfg2-conv-shaped" + tag, wl.conv_shaped(), "f32-mfma", "topk", 200, 20, prepared)
+        leg("paper-convolution" + tag, wl.paper_convolution(), "f32-mfma", "topk", 200, 20, prepared)
     return res
 
 

@@ -30,9 +30,9 @@ struct WsHeader {
   uint32_t work_counter;      // next chunk of the dynamic queue
   float bo_sum;               // sum of the members' output biases
   uint32_t n_live;            // entries of the live-chunk list (long constrained ranges)
-  uint32_t done;              // workgroups of the running sweep that have finished; the last one
-                              // puts tau, work_counter, n_live and done back to their idle values
-  uint32_t pad[10];
+  uint32_t done;              // workgroups of the running sweep that have finished (see self_reset)
+  uint32_t merge_done;        // workgroups of a two-stage merge launch that have written their list
+  uint32_t pad[9];
 };
 
 // Model shape and the layout of one packed member, in 32-bit words.
@@ -62,6 +62,8 @@ struct SweepParams {
   int32_t n_members, members_per_stage, n_stages, member_words;
   int32_t mode, k;
   int32_t merge;              // top-k: the caller's outputs hold a running result (values, indices, n_found)
+  int32_t self_reset;         // the last workgroup to finish restores the header's idle state (sweeps that
+                              // are the last kernel of their call and have used the header's counters)
   float inv_members;          // 1 / n_members, rounded once from double
   uint32_t cap, kp;           // pool capacity per workgroup, k rounded up to a power of two
   uint32_t lds_entries;       // keys that fit the LDS region after the space tables (weights / sort scratch)

@@ -18,6 +18,7 @@
 #pragma once
 #include "lane_ops.h"
 #include "sweep_common.h"
+#include "wave_sort.h"
 
 namespace tuner {
 
@@ -307,7 +308,19 @@ __global__ void __launch_bounds__(NW * 64) sweep_kernel(const SweepParams prm) {
     const uint32_t n = s_cnt;
     uint32_t n2 = next_pow2(n);
     n2 = n2 < prm.kp ? prm.kp : n2;
-    if (pool_in_lds) {
+    // up to 512 candidates (a short sweep: one chunk per workgroup) are sorted in registers,
+    // eight waves of 64 keys and three levels of merges, instead of the 45 barrier-separated
+    // steps of the workgroup-wide network
+    const bool small = kWaves >= 8 && n <= 512u && prm.kp <= 512u;
+    if (small && (pool_in_lds ? prm.lds_pool_entries >= 512u : lds_entries >= 512u)) {
+      unsigned long long* a = pool_in_lds ? lpool : lds_keys;
+      if (!pool_in_lds)
+        for (uint32_t x = tid; x < n; x += kThreads) a[x] = gpool[x];
+      for (uint32_t x = n + tid; x < 512u; x += kThreads) a[x] = kKeyMax;
+      __syncthreads();
+      sort512(a, prm.kp, tid);
+      for (uint32_t x = tid; x < prm.kp; x += kThreads) gpool[x] = a[x];
+    } else if (pool_in_lds) {
       for (uint32_t x = n + tid; x < n2; x += kThreads) lpool[x] = kKeyMax;
       __syncthreads();
       bitonic_sort(lpool, n2, tid, kThreads);
@@ -318,10 +331,12 @@ __global__ void __launch_bounds__(NW * 64) sweep_kernel(const SweepParams prm) {
       sort_pool(gpool, n2, lds_keys, lds_entries, tid, kThreads);
     }
   }
-  // The last workgroup to finish leaves the header as the next call expects it (every other
+  // A call on a prepared workspace has no kernel that resets the header before it.  Top-k
+  // calls leave that to their last merge launch; a sweep that is the last kernel of its call
+  // does it here: the last workgroup to finish restores the idle state (every other
   // workgroup's accesses to these words have completed: their results were consumed before
-  // the increment below), so that a call on a prepared workspace needs no reset kernel.
-  if (tid == 0) {
+  // the increment below).
+  if (prm.self_reset && tid == 0) {
     const uint32_t finished = atomicAdd(&prm.hdr->done, 1u);
     if (finished == gridDim.x - 1) {
       prm.hdr->work_counter = 0u;

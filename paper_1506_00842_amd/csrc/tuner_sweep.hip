@@ -31,6 +31,7 @@
 #include "net_valu.h"
 #include "sweep_common.h"
 #include "tuner_internal.h"
+#include "wave_sort.h"
 
 namespace tuner {
 
@@ -86,6 +87,7 @@ __global__ void __launch_bounds__(256) prep_kernel(const DevSpace sp, const Prep
     pp.hdr->work_counter = 0u;
     pp.hdr->n_live = 0u;
     pp.hdr->done = 0u;
+    pp.hdr->merge_done = 0u;
     pp.hdr->tau = kKeyMax;
   }
 }
@@ -110,55 +112,28 @@ empty_result_kernel(int32_t k, float* values, uint32_t* indices, int32_t* n_foun
 // outputs.  merge_kernel: one pair per workgroup, in place in global memory, for
 // lists too long for LDS.
 // ---------------------------------------------------------------------------
-constexpr uint32_t kWaveMergeMaxKp = 512;    // lists up to this long are merged one pair per wave
-
-// One wave merges two sorted lists of 64 * E keys in LDS (A, B) into the 64 * E smallest,
-// sorted, in A.  Lane l holds the keys i = l + 64 r: the steps of the merge network whose
-// partner index differs in r stay inside the lane, the others (strides below 64) exchange
-// registers between lanes; LDS is touched once for the load and once for the store.
-template <int E>
-__device__ __forceinline__ void wave_pair_merge(unsigned long long* A, const unsigned long long* B, uint32_t lane) {
-  constexpr uint32_t kp = 64u * E;
-  unsigned long long v[E];
-#pragma unroll
-  for (int r = 0; r < E; ++r) {
-    const uint32_t i = lane + 64u * r;
-    const unsigned long long a = A[i], b = B[kp - 1 - i];
-    v[r] = a < b ? a : b;
-  }
-#pragma unroll
-  for (int jr = E / 2; jr > 0; jr >>= 1)
-#pragma unroll
-    for (int r = 0; r < E; ++r)
-      if ((r & jr) == 0) {
-        const unsigned long long x = v[r], y = v[r | jr];
-        v[r] = x < y ? x : y;
-        v[r | jr] = x < y ? y : x;
-      }
-#pragma unroll
-  for (int j = 32; j > 0; j >>= 1) {
-    const bool upper = (lane & (uint32_t)j) != 0u;
-#pragma unroll
-    for (int r = 0; r < E; ++r) {
-      const unsigned long long o = __shfl_xor(v[r], j);
-      const bool take = upper ? (o > v[r]) : (o < v[r]);
-      v[r] = take ? o : v[r];
-    }
-  }
-#pragma unroll
-  for (int r = 0; r < E; ++r) A[lane + 64u * r] = v[r];
-}
+constexpr uint32_t kWaveMergeMaxKp = 512;    // lists up to this long are merged one pair per wave (wave_sort.h)
 
 struct MergeParams {
   unsigned long long* pools;
   unsigned long long* extra;   // list index n_pool_lists (the caller's running result)
   uint32_t cap, n_pool_lists, n_lists, kp;
   uint32_t stride0, levels;
+  uint32_t fuse_levels;        // > 0: the last workgroup to finish merges the launch's 2^fuse_levels results
   int32_t final, k;
   float* values;
   uint32_t* indices;
   int32_t* n_found;
+  WsHeader* hdr;               // final launch: the header goes back to its idle state for the next call
 };
+
+__device__ __forceinline__ void reset_header(WsHeader* hdr) {
+  hdr->work_counter = 0u;
+  hdr->n_live = 0u;
+  hdr->done = 0u;
+  hdr->merge_done = 0u;
+  hdr->tau = kKeyMax;
+}
 
 __device__ __forceinline__ void emit_result(const unsigned long long* list, int i, int32_t k, float* values,
                                             uint32_t* indices, int32_t* n_found) {
@@ -170,20 +145,40 @@ __device__ __forceinline__ void emit_result(const unsigned long long* list, int 
   if (real && (i == k - 1 || list[i + 1] == kKeyMax)) *n_found = i + 1;
 }
 
-__global__ void __launch_bounds__(kMergeThreads) merge_tree_kernel(const MergeParams mp) {
-  extern __shared__ __align__(16) unsigned char merge_smem[];
-  unsigned long long* lds = reinterpret_cast<unsigned long long*>(merge_smem);
-  const uint32_t tid = threadIdx.x, kp = mp.kp;
-  const uint32_t slots = 1u << mp.levels;
-  const uint32_t base = blockIdx.x * mp.stride0 * slots;
-  auto list_ptr = [&](uint32_t j) -> unsigned long long* {
+// Loads the lists first + j * stride (j = 0 .. 2^levels - 1; indices >= n_lists read as empty)
+// into LDS slots of kp keys: all lists at once, many loads in flight per thread (a loop over
+// the lists would pay one memory latency per list): 8 x 16 bytes per thread and round, which
+// covers 32 lists of 512 keys in one round.
+// COHERENT: the lists were written during this launch by other workgroups (agent-scope
+// atomic stores); they are read with agent-scope atomic loads, which are performed at the
+// device's coherence point, past the L2 of the XCD this workgroup runs on.
+template <bool COHERENT>
+__device__ __forceinline__ void merge_load(const MergeParams& mp, unsigned long long* lds, uint32_t first,
+                                           uint32_t stride, uint32_t slots, uint32_t n_lists, uint32_t tid) {
+  const uint32_t kp = mp.kp;
+  auto list_ptr = [&](uint32_t j) -> const unsigned long long* {
     return j < mp.n_pool_lists ? mp.pools + (size_t)j * mp.cap : mp.extra;
   };
-  // all lists at once, many loads in flight per thread (a loop over the lists would pay
-  // one memory latency per list): 8 x 16 bytes per thread and round, which covers 32 lists
-  // of 512 keys in one round
   const uint32_t total = slots * kp;
-  if ((kp & 1u) == 0u) {
+  if constexpr (COHERENT) {
+    for (uint32_t t0 = 0; t0 < total; t0 += 8 * kMergeThreads) {
+      unsigned long long v[8];
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        const uint32_t t = t0 + q * kMergeThreads + tid;
+        const uint32_t j = t / kp, x = t - j * kp;
+        const uint32_t li = first + j * stride;
+        v[q] = kKeyMax;
+        if (t < total && li < n_lists)
+          v[q] = __hip_atomic_load(list_ptr(li) + x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        const uint32_t t = t0 + q * kMergeThreads + tid;
+        if (t < total) lds[t] = v[q];
+      }
+    }
+  } else if ((kp & 1u) == 0u) {
     const uint32_t kp2 = kp >> 1, total2 = total >> 1;
     ulonglong2* lds2 = reinterpret_cast<ulonglong2*>(lds);
     for (uint32_t t0 = 0; t0 < total2; t0 += 8 * kMergeThreads) {
@@ -192,9 +187,9 @@ __global__ void __launch_bounds__(kMergeThreads) merge_tree_kernel(const MergePa
       for (int q = 0; q < 8; ++q) {
         const uint32_t t = t0 + q * kMergeThreads + tid;
         const uint32_t j = t / kp2, x = t - j * kp2;
-        const uint32_t li = base + j * mp.stride0;
+        const uint32_t li = first + j * stride;
         v[q] = make_ulonglong2(kKeyMax, kKeyMax);
-        if (t < total2 && li < mp.n_lists) v[q] = reinterpret_cast<const ulonglong2*>(list_ptr(li))[x];
+        if (t < total2 && li < n_lists) v[q] = reinterpret_cast<const ulonglong2*>(list_ptr(li))[x];
       }
 #pragma unroll
       for (int q = 0; q < 8; ++q) {
@@ -204,11 +199,16 @@ __global__ void __launch_bounds__(kMergeThreads) merge_tree_kernel(const MergePa
     }
   } else {                                   // kp = 1
     for (uint32_t t = tid; t < total; t += kMergeThreads) {
-      const uint32_t li = base + t * mp.stride0;
-      lds[t] = li < mp.n_lists ? list_ptr(li)[0] : kKeyMax;
+      const uint32_t li = first + t * stride;
+      lds[t] = li < n_lists ? list_ptr(li)[0] : kKeyMax;
     }
   }
   __syncthreads();
+}
+
+// Merges the `slots` sorted lists of kp keys in LDS pairwise, level by level; the kp smallest
+// keys of all of them end up sorted in slot 0.
+__device__ __forceinline__ void merge_levels(unsigned long long* lds, uint32_t kp, uint32_t slots, uint32_t tid) {
   const uint32_t half = kp >> 1;
   if (kp >= 64 && kp <= kWaveMergeMaxKp) {
     // Lists of 64 .. 512 keys: one wave per pair of lists, the merge network in registers;
@@ -255,36 +255,70 @@ __global__ void __launch_bounds__(kMergeThreads) merge_tree_kernel(const MergePa
       __syncthreads();
     }
   } else {
-  for (uint32_t s = 1; s < slots; s <<= 1) {
-    const uint32_t npairs = slots / (2 * s);
-    // A[i] = min(A[i], B[kp-1-i]) over every pair (A = slot 2 m s, B = slot 2 m s + s)
-    for (uint32_t t = tid; t < npairs * kp; t += kMergeThreads) {
-      const uint32_t m = t / kp, i = t - m * kp;
-      unsigned long long* A = lds + (size_t)(2 * m * s) * kp;
-      const unsigned long long a = A[i], b = A[(size_t)s * kp + (kp - 1 - i)];
-      A[i] = a < b ? a : b;
-    }
-    __syncthreads();
-    for (uint32_t j = half; j > 0; j >>= 1) {
-      for (uint32_t t = tid; t < npairs * half; t += kMergeThreads) {
-        const uint32_t m = t / half, u = t - m * half;
+    for (uint32_t s = 1; s < slots; s <<= 1) {
+      const uint32_t npairs = slots / (2 * s);
+      // A[i] = min(A[i], B[kp-1-i]) over every pair (A = slot 2 m s, B = slot 2 m s + s)
+      for (uint32_t t = tid; t < npairs * kp; t += kMergeThreads) {
+        const uint32_t m = t / kp, i = t - m * kp;
         unsigned long long* A = lds + (size_t)(2 * m * s) * kp;
-        const uint32_t i = ((u & ~(j - 1)) << 1) | (u & (j - 1));
-        const uint32_t l = i | j;
-        const unsigned long long x = A[i], y = A[l];
-        if (x > y) { A[i] = y; A[l] = x; }
+        const unsigned long long a = A[i], b = A[(size_t)s * kp + (kp - 1 - i)];
+        A[i] = a < b ? a : b;
       }
       __syncthreads();
+      for (uint32_t j = half; j > 0; j >>= 1) {
+        for (uint32_t t = tid; t < npairs * half; t += kMergeThreads) {
+          const uint32_t m = t / half, u = t - m * half;
+          unsigned long long* A = lds + (size_t)(2 * m * s) * kp;
+          const uint32_t i = ((u & ~(j - 1)) << 1) | (u & (j - 1));
+          const uint32_t l = i | j;
+          const unsigned long long x = A[i], y = A[l];
+          if (x > y) { A[i] = y; A[l] = x; }
+        }
+        __syncthreads();
+      }
     }
   }
+}
+
+__global__ void __launch_bounds__(kMergeThreads) merge_tree_kernel(const MergeParams mp) {
+  extern __shared__ __align__(16) unsigned char merge_smem[];
+  __shared__ uint32_t s_last;
+  unsigned long long* lds = reinterpret_cast<unsigned long long*>(merge_smem);
+  const uint32_t tid = threadIdx.x, kp = mp.kp;
+  const uint32_t slots = 1u << mp.levels;
+  const uint32_t base = blockIdx.x * mp.stride0 * slots;
+  merge_load<false>(mp, lds, base, mp.stride0, slots, mp.n_lists, tid);
+  merge_levels(lds, kp, slots, tid);
+  if (!mp.final) {
+    unsigned long long* dst = base < mp.n_pool_lists ? mp.pools + (size_t)base * mp.cap : mp.extra;
+    if (!mp.fuse_levels) {
+      for (uint32_t x = tid; x < kp; x += kMergeThreads) dst[x] = lds[x];
+      return;
+    }
+    // Second stage in the same launch: the workgroup that finishes last merges the lists the
+    // others have written.  The workgroups may sit on different XCDs, each with an L2 of its
+    // own, so the lists and the counter travel as agent-scope atomic stores and loads
+    // (performed at the device's coherence point), ordered by s_waitcnt vmcnt(0) + the
+    // workgroup barrier on the writers' side and by the barrier on the reader's side; no L2
+    // write-back or invalidate is issued.
+    for (uint32_t x = tid; x < kp; x += kMergeThreads)
+      __hip_atomic_store(&dst[x], lds[x], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0): this wave's stores have been performed
+    __syncthreads();
+    if (tid == 0)
+      s_last = __hip_atomic_fetch_add(&mp.hdr->merge_done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == gridDim.x - 1
+                   ? 1u : 0u;
+    __syncthreads();
+    if (!s_last) return;
+    const uint32_t stride1 = mp.stride0 * slots;
+    merge_load<true>(mp, lds, 0, stride1, 1u << mp.fuse_levels,
+                     gridDim.x * stride1 < mp.n_lists ? gridDim.x * stride1 : mp.n_lists, tid);
+    merge_levels(lds, kp, 1u << mp.fuse_levels, tid);
   }
-  unsigned long long* dst = list_ptr(base);
-  for (uint32_t x = tid; x < kp; x += kMergeThreads) dst[x] = lds[x];
-  if (mp.final) {
-    // slot 0 holds kp >= k sorted keys; one more sentinel for the look-ahead at k - 1
-    for (int i = (int)tid; i < mp.k; i += kMergeThreads)
-      emit_result(lds, i, mp.k, mp.values, mp.indices, mp.n_found);
-  }
+  // slot 0 holds kp >= k sorted keys: the caller's outputs
+  for (int i = (int)tid; i < mp.k; i += kMergeThreads)
+    emit_result(lds, i, mp.k, mp.values, mp.indices, mp.n_found);
+  if (tid == 0) reset_header(mp.hdr);
 }
 
 __global__ void __launch_bounds__(kMergeThreads)
@@ -312,9 +346,10 @@ merge_kernel(unsigned long long* pools, uint32_t cap, unsigned long long* extra,
 
 __global__ void __launch_bounds__(256)
 finalize_kernel(const unsigned long long* list, int32_t k, float* values, uint32_t* indices,
-                int32_t* n_found) {
+                int32_t* n_found, WsHeader* hdr) {
   for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < k; i += gridDim.x * blockDim.x)
     emit_result(list, i, k, values, indices, n_found);
+  if (blockIdx.x == 0 && threadIdx.x == 0) reset_header(hdr);
 }
 
 // ---------------------------------------------------------------------------
@@ -670,6 +705,16 @@ struct SweepPlan {
   int merge_launches = 0;
 };
 
+// A merge launch of `blocks` workgroups can finish the merge itself (its last workgroup merges
+// the blocks' results) when those results fit the LDS of one workgroup: the number of tree
+// levels of that second stage, or 0.
+static uint32_t merge_fuse_levels(uint32_t blocks, size_t list_bytes, size_t lds_max) {
+  if (blocks < 2) return 0;
+  uint32_t levels = 1;
+  while ((1u << levels) < blocks) ++levels;
+  return (list_bytes << levels) <= lds_max ? levels : 0;
+}
+
 static int plan_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin, uint64_t count, int mode,
                       int k, bool index_list, const DeviceInfo& di, SweepPlan* out) {
   SweepPlan& P = *out;
@@ -797,6 +842,7 @@ static int plan_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begi
         while (levels < P.merge_max_levels && (1u << levels) < live) ++levels;
         live = (live + (1u << levels) - 1) >> levels;
         ++P.merge_launches;
+        if (live > 1 && merge_fuse_levels(live, list_bytes, P.merge_lds_max)) break;   // second stage in the same launch
       }
       if (n_lists == 1) P.merge_launches = 1;      // finalize only
     } else {
@@ -890,6 +936,7 @@ static int run_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin
     sw.off = NetOffsets{sh.o_w1, sh.o_w2, sh.o_b1, sh.o_b2, sh.o_wo, sh.H1, sh.H2, sh.o_wh, sh.p0};
     sw.mode = mode;
     sw.merge = merge;
+    sw.self_reset = (mode == MODE_ALL && (P.dynamic || P.use_live)) ? 1 : 0;
     sw.extra = mode == MODE_TOPK ? extra : nullptr;
     sw.run_values = values;
     sw.run_indices = indices;
@@ -953,6 +1000,7 @@ static int run_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin
         uint32_t levels = 1;
         while (levels < P.merge_max_levels && (1u << levels) < live) ++levels;
         const uint32_t blocks = (live + (1u << levels) - 1) >> levels;
+        const uint32_t fuse = merge_fuse_levels(blocks, list_bytes, P.merge_lds_max);
         MergeParams mp{};
         mp.pools = pools;
         mp.extra = extra;
@@ -962,15 +1010,18 @@ static int run_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin
         mp.kp = L.kp;
         mp.stride0 = stride;
         mp.levels = levels;
+        mp.fuse_levels = fuse;
         mp.final = blocks == 1 ? 1 : 0;
         mp.k = k;
         mp.values = values;
         mp.indices = indices;
         mp.n_found = n_found;
-        hipLaunchKernelGGL(merge_tree_kernel, dim3(blocks), dim3(kMergeThreads), list_bytes << levels, stream, mp);
+        mp.hdr = hdr;
+        hipLaunchKernelGGL(merge_tree_kernel, dim3(blocks), dim3(kMergeThreads),
+                           list_bytes << std::max(levels, fuse), stream, mp);
         TUNER_HIP_TRY(hipGetLastError());
-        finalized = blocks == 1;
-        live = blocks;
+        finalized = blocks == 1 || fuse > 0;
+        live = fuse > 0 ? 1 : blocks;
         stride <<= levels;
       }
     } else {
@@ -986,7 +1037,7 @@ static int run_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin
     if (!finalized) {
       const unsigned long long* list0 = groups > 0 ? pools : extra;
       hipLaunchKernelGGL(finalize_kernel, dim3((k + 255) / 256), dim3(256), 0, stream, list0, k, values,
-                         indices, n_found);
+                         indices, n_found, hdr);
       TUNER_HIP_TRY(hipGetLastError());
     }
   }
