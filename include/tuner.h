@@ -307,8 +307,12 @@ int tuner_decode_range(const tuner_space* space, uint64_t index_begin, uint64_t 
 /*
  * Ensemble evaluation at an arbitrary list of configurations (the held-out
  * configurations of Section 6, first paragraph; the training samples of
- * Section 5.2): same arithmetic as tuner_predict_all, with configuration
- * indices read from a list instead of a range.
+ * Section 5.2): the same network evaluation as tuner_predict_all, with
+ * configuration indices read from a list instead of a range.  A range sweep
+ * may compute layer 1 in a different order (see tuner_hoisted_parameters and
+ * tuner_tabulated_parameters), so for the same configuration the two agree
+ * within the fp32 tolerance (a few 1e-7 relative), not bit for bit; each of
+ * them is repeatable bit for bit.
  *   indices_dev      DEVICE, n uint32 configuration indices (each < N; an index
  *                    outside the space is not detected)
  *   predictions_dev  DEVICE, n floats; +INF where the configuration is invalid
