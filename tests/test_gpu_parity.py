@@ -552,3 +552,56 @@ def test_prepared_calls_equal_plain_calls(maker, kw_name):
     torch.cuda.synchronize()
     gv2, gi2 = sw.topk_host()
     assert np.array_equal(gi, gi2) and np.array_equal(gv, gv2)
+
+
+def test_prepared_and_static_calls_replay_from_a_hip_graph():
+    """The callers the prepared and the static-scratch entry points are for: a captured
+    sequence of sweeps replayed many times.  Every replay (with eager sweeps on the same
+    workspace and scribbled outputs in between) reproduces the eager result bit for bit:
+    the header's counters are back in their idle state after every call."""
+    import paper_1506_00842_amd as T
+    w = wl.paper_stereo()                      # long enough for the work queue and the live-chunk list
+    n = w.space.n_configs
+    cut = n // 2 + 4321
+    sw = sweep_for(w)
+    sw.topk(0, cut)
+    sw.topk(cut, n - cut, merge=True)
+    torch.cuda.synchronize()
+    ref_v, ref_i = sw.values.clone(), sw.indices.clone()
+    oy, ov, _ = oracle.predict_range(w.space, w.model, 0, n, threads=THREADS)
+    gv, gi = sw.topk_host()
+    parity.check_topk(gv, gi, oy, ov, 0, w.k)
+    sw.prepare()
+    sv = torch.empty_like(sw.values)
+    si = torch.empty_like(sw.indices)
+    sn = torch.zeros_like(sw.n_found)
+
+    def static_calls():
+        T.tuner_predict_topk_static(sw.space, sw.model, 0, cut, w.k, 0, sv, si, sn)
+        T.tuner_predict_topk_static(sw.space, sw.model, cut, n - cut, w.k, 1, sv, si, sn)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):              # warm-up on the capture stream (first use of the static array too)
+        sw.topk(0, cut)
+        static_calls()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        sw.topk(0, cut)                        # prepared calls: sweep (+ classification) and one merge launch each
+        sw.topk(cut, n - cut, merge=True)
+        static_calls()
+    for rep in range(4):
+        sw.values.fill_(-1.0)
+        sw.indices.fill_(7)
+        sw.n_found.fill_(0)
+        sv.fill_(-2.0)
+        si.fill_(9)
+        sw.topk(rep * 1000, 300000 + rep)      # eager prepared call on the same workspace
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(sw.values.view(torch.int32), ref_v.view(torch.int32)) and torch.equal(sw.indices, ref_i), f"replay {rep}"
+        assert torch.equal(sv.view(torch.int32), ref_v.view(torch.int32)) and torch.equal(si, ref_i), f"replay {rep}"
+        assert int(sn.item()) == w.k
