@@ -129,6 +129,37 @@ __global__ void __launch_bounds__(NW * 64) sweep_kernel(const SweepParams prm) {
   // chunks to sweep, made by classify_kernel: runs of chunks without any valid
   // configuration would otherwise turn the queue counter into the bottleneck (every
   // workgroup claims such units as fast as the atomic unit serves them).
+  // Leaves the smallest keys of the pool's n candidates sorted at its front: at least
+  // max(kp, what the pool held) of them when everything was sorted, else the kp smallest,
+  // followed by padding keys up to kp.  Lists of up to 512 keys (k <= 512) go through the
+  // register-level selection (a barrier per merge level); longer ones through the
+  // workgroup-wide sorting network.  A pool in the workspace is sorted in the LDS region of
+  // the weights when it fits there (the resident ensemble is then loaded again).
+  auto sort_candidates = [&](uint32_t n, bool sweep_goes_on) {
+    uint32_t n2 = next_pow2(n);
+    n2 = n2 < prm.kp ? prm.kp : n2;
+    const uint32_t keep = prm.kp < 64u ? 64u : prm.kp;
+    const bool select = prm.kp <= kSelectMaxKeep;
+    const uint32_t m2 = (select && n2 < 64u) ? 64u : n2;       // the selection works on runs of 64 keys
+    if (pool_in_lds) {
+      for (uint32_t x = n + tid; x < m2; x += kThreads) lpool[x] = kKeyMax;
+      __syncthreads();
+      if (select && m2 <= prm.lds_pool_entries) select_sorted(lpool, m2, keep, tid, kThreads);
+      else bitonic_sort(lpool, n2, tid, kThreads);
+    } else if (select && m2 <= lds_entries) {
+      for (uint32_t x = tid; x < m2; x += kThreads) lds_keys[x] = x < n ? gpool[x] : kKeyMax;
+      __syncthreads();
+      select_sorted(lds_keys, m2, keep, tid, kThreads);
+      for (uint32_t x = tid; x < prm.kp; x += kThreads) gpool[x] = lds_keys[x];
+      __syncthreads();
+      if (sweep_goes_on && prm.n_stages == 1) load_stage(0);    // the scratch held the weights
+    } else {
+      for (uint32_t x = n + tid; x < n2; x += kThreads) gpool[x] = kKeyMax;
+      __syncthreads();
+      sort_pool(gpool, n2, lds_keys, lds_entries, tid, kThreads);
+      if (sweep_goes_on && prm.n_stages == 1 && n2 <= lds_entries) load_stage(0);   // scratch held the weights
+    }
+  };
   const bool dynamic = prm.dynamic != 0;
   const uint32_t n_chunks = prm.live ? prm.hdr->n_live : prm.n_chunks;
   const uint32_t n_units = prm.live ? (n_chunks + (uint32_t)prm.super - 1u) / (uint32_t)prm.super : prm.n_units;
@@ -160,17 +191,7 @@ __global__ void __launch_bounds__(NW * 64) sweep_kernel(const SweepParams prm) {
     if (prm.mode == MODE_TOPK && s_compact) {
       // pool nearly full: keep its k smallest keys, lower the thresholds
       const uint32_t n = s_cnt;
-      const uint32_t n2 = next_pow2(n);
-      if (pool_in_lds) {
-        for (uint32_t x = n + tid; x < n2; x += kThreads) lpool[x] = kKeyMax;
-        __syncthreads();
-        bitonic_sort(lpool, n2, tid, kThreads);
-      } else {
-        for (uint32_t x = n + tid; x < n2; x += kThreads) gpool[x] = kKeyMax;
-        __syncthreads();
-        sort_pool(gpool, n2, lds_keys, lds_entries, tid, kThreads);
-        if (prm.n_stages == 1 && n2 <= lds_entries) load_stage(0);   // scratch held the weights
-      }
+      sort_candidates(n, true);
       if (tid == 0) {
         if (n >= (uint32_t)prm.k) {
           const unsigned long long t = pool_in_lds ? lpool[prm.k - 1] : gpool[prm.k - 1];
@@ -306,30 +327,9 @@ __global__ void __launch_bounds__(NW * 64) sweep_kernel(const SweepParams prm) {
     // final: sorted list of at least kp entries (padded with the sentinel)
     __syncthreads();
     const uint32_t n = s_cnt;
-    uint32_t n2 = next_pow2(n);
-    n2 = n2 < prm.kp ? prm.kp : n2;
-    // up to 512 candidates (a short sweep: one chunk per workgroup) are sorted in registers,
-    // eight waves of 64 keys and three levels of merges, instead of the 45 barrier-separated
-    // steps of the workgroup-wide network
-    const bool small = kWaves >= 8 && n <= 512u && prm.kp <= 512u;
-    if (small && (pool_in_lds ? prm.lds_pool_entries >= 512u : lds_entries >= 512u)) {
-      unsigned long long* a = pool_in_lds ? lpool : lds_keys;
-      if (!pool_in_lds)
-        for (uint32_t x = tid; x < n; x += kThreads) a[x] = gpool[x];
-      for (uint32_t x = n + tid; x < 512u; x += kThreads) a[x] = kKeyMax;
-      __syncthreads();
-      sort512(a, prm.kp, tid);
-      for (uint32_t x = tid; x < prm.kp; x += kThreads) gpool[x] = a[x];
-    } else if (pool_in_lds) {
-      for (uint32_t x = n + tid; x < n2; x += kThreads) lpool[x] = kKeyMax;
-      __syncthreads();
-      bitonic_sort(lpool, n2, tid, kThreads);
+    sort_candidates(n, false);
+    if (pool_in_lds)
       for (uint32_t x = tid; x < prm.kp; x += kThreads) gpool[x] = lpool[x];
-    } else {
-      for (uint32_t x = n + tid; x < n2; x += kThreads) gpool[x] = kKeyMax;
-      __syncthreads();
-      sort_pool(gpool, n2, lds_keys, lds_entries, tid, kThreads);
-    }
   }
   // A call on a prepared workspace has no kernel that resets the header before it.  Top-k
   // calls leave that to their last merge launch; a sweep that is the last kernel of its call

@@ -176,22 +176,42 @@ __device__ __forceinline__ unsigned long long wave_sort64(unsigned long long key
   return v[0];
 }
 
-// The whole workgroup sorts a[0 .. 512) in LDS (unused entries hold the largest key) and
-// leaves the `keep` smallest (256 or 512) sorted at the front: eight waves sort 64 keys each
-// in registers, then three levels of pairwise merges, one wave per pair.
-__device__ inline void sort512(unsigned long long* a, uint32_t keep, int tid) {
-  const uint32_t wave = (uint32_t)tid >> 6, lane = (uint32_t)tid & 63u;
-  if (wave < 8) a[wave * 64 + lane] = wave_sort64(a[wave * 64 + lane], lane);
+// The whole workgroup leaves the `keep` smallest keys of a[0 .. n2) sorted at the front of a
+// (LDS; n2 a power of two >= 64, unused entries hold the largest key; keep = 64, 128, 256 or
+// 512, at most n2).  Every wave sorts runs of 64 keys in registers; then levels of pairwise
+// merges, one wave per pair: two runs become one of twice the length until the runs are `keep`
+// long, after that a pair leaves its `keep` smallest keys in its first run.  One workgroup
+// barrier per level instead of one per step of a workgroup-wide sorting network.
+constexpr uint32_t kSelectMaxKeep = 512;
+
+__device__ inline void select_sorted(unsigned long long* a, uint32_t n2, uint32_t keep, int tid, int nthreads) {
+  const uint32_t wave = (uint32_t)tid >> 6, lane = (uint32_t)tid & 63u, nwaves = (uint32_t)nthreads >> 6;
+  uint32_t runs = n2 >> 6;
+  for (uint32_t r = wave; r < runs; r += nwaves) a[r * 64 + lane] = wave_sort64(a[r * 64 + lane], lane);
   __syncthreads();
-  if (wave < 4) wave_full_merge<2>(a + wave * 128, a + wave * 128 + 64, a + wave * 128, lane);
-  __syncthreads();
-  if (wave < 2) wave_full_merge<4>(a + wave * 256, a + wave * 256 + 128, a + wave * 256, lane);
-  __syncthreads();
-  if (wave == 0) {
-    if (keep > 256) wave_full_merge<8>(a, a + 256, a, lane);
-    else wave_pair_merge<4>(a, a + 256, lane);
+  uint32_t len = 64, stride = 64;                 // run length; distance between the starts of two runs
+  while (runs > 1) {
+    const uint32_t pairs = runs >> 1;
+    const bool grow = 2 * len <= keep;
+    for (uint32_t p = wave; p < pairs; p += nwaves) {
+      unsigned long long* A = a + (size_t)(2 * p) * stride;
+      unsigned long long* B = A + stride;
+      if (grow) {                                 // stride == len here: B follows A directly
+        if (len == 64) wave_full_merge<2>(A, B, A, lane);
+        else if (len == 128) wave_full_merge<4>(A, B, A, lane);
+        else wave_full_merge<8>(A, B, A, lane);
+      } else {
+        if (len == 64) wave_pair_merge<1>(A, B, lane);
+        else if (len == 128) wave_pair_merge<2>(A, B, lane);
+        else if (len == 256) wave_pair_merge<4>(A, B, lane);
+        else wave_pair_merge<8>(A, B, lane);
+      }
+    }
+    __syncthreads();
+    if (grow) len <<= 1;
+    stride <<= 1;
+    runs = pairs;
   }
-  __syncthreads();
 }
 
 }  // namespace tuner
