@@ -229,6 +229,10 @@ def test_sweep_plan_of_the_benchmark_configurations():
     p = plan(wc, 0, wc.space.n_configs, 200)
     assert p["tiles_per_wave"] == 1 and p["workgroups"] == 256 and p["n_units"] == 256
     assert p["dynamic_queue"] == 0 and p["live_chunk_list"] == 0
+    # 257 lists of 256 keys: 9 workgroups merge 32 lists each, the last of them to finish merges
+    # the nine results in the same launch; lists of 1024 keys (k = 1000) take 257 -> 17, then 17 -> 2 -> 1
+    assert p["merge_launches"] == 1
+    assert plan(wl.large(), 0, 1 << 27, 1000)["merge_launches"] == 2
     # an empty range launches no sweep
     p = plan(wc, 77, 0, 200)
     assert p["workgroups"] == 0 and p["n_chunks"] == 0
