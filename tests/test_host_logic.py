@@ -265,6 +265,36 @@ def test_static_scratch_entry_point_argument_errors():
     assert T.TUNER_STATIC_SCRATCH_BYTES == 64 << 20
 
 
+def test_prepare_and_prepared_calls_argument_errors():
+    """tuner_prepare and the prepared entry points reject bad calls on the host like the calls
+    they replace (no kernel is reached on a machine without a GPU)."""
+    L = T.load_library()
+    w = wl.paper_convolution()
+    h = make_space(w.space)
+    m = T.ModelHandle(11, w.model.widths, _FakeWeights())
+    fake = C.c_void_p(0x4000)
+    need = T.tuner_workspace_bytes(h, m, 200)
+    assert L.tuner_prepare(None, C.byref(m.c), fake, need, None) == T.TUNER_EINVAL
+    assert L.tuner_prepare(h.ptr, None, fake, need, None) == T.TUNER_EINVAL
+    assert L.tuner_prepare(h.ptr, C.byref(m.c), None, need, None) == T.TUNER_EWORKSPACE
+    assert L.tuner_prepare(h.ptr, C.byref(m.c), fake, 1024, None) == T.TUNER_EWORKSPACE
+    assert L.tuner_prepare(h.ptr, C.byref(m.c), C.c_void_p(0x4010), need, None) == T.TUNER_EWORKSPACE
+    bad = T.ModelHandle(11, [8, 30, 1], _FakeWeights())
+    assert L.tuner_prepare(h.ptr, C.byref(bad.c), fake, need, None) == T.TUNER_EINVAL
+    # header, tables and packed weights need far less than a top-k workspace
+    assert T.tuner_workspace_bytes(h, m, 0) < need
+    tk = L.tuner_predict_topk_prepared
+    assert tk(h.ptr, C.byref(m.c), 0, 100, 200, 0, None, fake, fake, fake, need, None) == T.TUNER_EINVAL
+    assert tk(h.ptr, C.byref(m.c), 0, 100, 0, 0, fake, fake, fake, fake, need, None) == T.TUNER_EINVAL
+    assert tk(h.ptr, C.byref(m.c), 0, 100, T.TUNER_MAX_K + 1, 0, fake, fake, fake, fake, need, None) == T.TUNER_ETOOLARGE
+    assert tk(h.ptr, C.byref(m.c), 131072 - 5, 6, 200, 0, fake, fake, fake, fake, need, None) == T.TUNER_EINVAL
+    assert tk(h.ptr, C.byref(m.c), 0, 100, 200, 0, fake, fake, fake, fake, need - 1, None) == T.TUNER_EWORKSPACE
+    pa = L.tuner_predict_all_prepared
+    assert pa(h.ptr, C.byref(m.c), 0, 100, None, None, fake, need, None) == T.TUNER_EINVAL
+    assert pa(h.ptr, C.byref(m.c), 0, 100, fake, None, None, need, None) == T.TUNER_EWORKSPACE
+    assert pa(h.ptr, C.byref(m.c), 131072, 1, fake, None, fake, need, None) == T.TUNER_EINVAL
+
+
 def test_profile_events_are_dropped_when_profiling_is_switched_off():
     T.tuner_profile_enable(True)
     assert T.tuner_profile_pending() == 0
