@@ -406,9 +406,11 @@ def test_topk_repeatable_and_k_max():
     parity.check_topk(res[0][0], res[0][1], oy, ov, 0, 16384)
 
 
-def test_adversarial_order_descending_predictions():
+@pytest.mark.parametrize("k", [1, 64, 300, 512, 1000])
+def test_adversarial_order_descending_predictions(k):
     """Predictions that decrease with the index make every configuration pass
-    the running threshold: exercises pool compaction under maximum pressure."""
+    the running threshold: exercises pool compaction under maximum pressure (k <= 512:
+    selection in registers at every compaction; above: the workgroup-wide sort)."""
     sp = wl.Space("desc", [[float(v) for v in range(1, 65)]] * 3, [wl.SCALE_LINEAR] * 3)
     # y = -(256 sigmoid(2 x0) + sigmoid(2 x1)): non-increasing in the index, and every
     # new (x0, x1) group lies below everything seen before it
@@ -421,7 +423,7 @@ def test_adversarial_order_descending_predictions():
     Wh[1, 1] = 2.0
     wo[0, 0] = -256.0
     wo[0, 1] = -1.0
-    w = wl.Workload("desc", sp, m, 1000)
+    w = wl.Workload("desc", sp, m, k)
     n = sp.n_configs
     oy, ov, _ = oracle.predict_range(sp, m, 0, n, threads=THREADS)
     assert np.all(np.diff(oy.astype(np.float64)) <= 0)
@@ -429,7 +431,29 @@ def test_adversarial_order_descending_predictions():
     sw.topk(0, n)
     torch.cuda.synchronize()
     gv, gi = sw.topk_host()
-    parity.check_topk(gv, gi, oy, ov, 0, 1000)
+    parity.check_topk(gv, gi, oy, ov, 0, k)
+
+
+@pytest.mark.parametrize("net", ["f32", "split16", "bf16"])
+def test_topk_small_k_with_several_chunks_per_workgroup_on_wide_nets(net):
+    """128-wide networks run in workgroups of 8 (fp32, two-plane f16) or 16 (bf16) waves;
+    their candidate pools lie in the workspace (fp32; two-plane f16 from k = 512) or in LDS,
+    and a sort of a workspace pool borrows the LDS that holds the weights.  2^19
+    configurations are two to eight chunks for each of the 256 workgroups, so pools are cut
+    back while the sweep goes on.  k on both sides of the limit of the selection in registers."""
+    kw, tol = ({}, parity.TOL_FP32) if net == "f32" else _nets()[net]
+    sp = wl.large().space
+    m = wl.make_model([14, 128, 128, 1], 2, 77)
+    begin, count = (5 << 21) + (3 << 18) + 12345, 1 << 19
+    oy, ov, _ = oracle.predict_range(sp, m, begin, count, threads=THREADS)
+    assert 0 < int(ov.sum()) < count
+    for k in (1, 100, 512, 700):
+        sw = sweep_for(wl.Workload("wide2", sp, m, k), **kw)
+        sw.topk(begin, count)
+        torch.cuda.synchronize()
+        gv, gi = sw.topk_host()
+        parity.check_topk(gv, gi, oy, ov, begin, k, tol=tol)
+        say(f"  {net} k={k}: ok, {len(gi)} found")
 
 
 def test_topk_and_predict_all_replay_from_a_hip_graph():
