@@ -196,7 +196,8 @@ typedef struct {
   int32_t double_buffer;          /* the next stage loads while the current one is evaluated */
   int32_t pool_in_lds;            /* the workgroup's candidate pool lives in LDS */
   int32_t lds_bytes;              /* dynamic LDS of the sweep kernel */
-  int32_t merge_launches;         /* kernels after the sweep (top-k) */
+  int32_t merge_launches;         /* kernels after the sweep (top-k, merge = 0; the running result
+                                     of a merging call is one more list and can add a launch) */
   size_t workspace_bytes;         /* workspace the call itself needs (<= tuner_workspace_bytes) */
 } tuner_sweep_plan_info;
 int tuner_sweep_plan(const tuner_space* space, const tuner_model* model, uint64_t index_begin,

@@ -702,6 +702,7 @@ struct SweepPlan {
   bool merge_in_lds = false;
   uint32_t merge_max_levels = 0;
   size_t merge_lds_max = 0;
+  uint32_t n_lists = 0;                // the workgroups' lists, and the running result when the call merges with it
   int merge_launches = 0;
 };
 
@@ -716,7 +717,7 @@ static uint32_t merge_fuse_levels(uint32_t blocks, size_t list_bytes, size_t lds
 }
 
 static int plan_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin, uint64_t count, int mode,
-                      int k, bool index_list, const DeviceInfo& di, SweepPlan* out) {
+                      int k, bool merge, bool index_list, const DeviceInfo& di, SweepPlan* out) {
   SweepPlan& P = *out;
   int rc = choose_shape(sp, m, !index_list, di.max_lds, &P.sh, &P.var);
   if (rc) return rc;
@@ -826,8 +827,9 @@ static int plan_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begi
   }
 
   if (mode == MODE_TOPK) {
-    // lists: pool 0..groups-1, then the running result
-    const uint32_t n_lists = P.groups + 1;
+    // lists: pool 0..groups-1, then the running result when it takes part
+    const uint32_t n_lists = P.groups + (merge || P.groups == 0 ? 1u : 0u);
+    P.n_lists = n_lists;
     const size_t list_bytes = (size_t)P.L.kp * 8;
     P.merge_lds_max = std::min<size_t>((size_t)di.max_lds, 128u << 10);
     P.merge_in_lds = 2 * list_bytes <= P.merge_lds_max;
@@ -871,7 +873,7 @@ static int run_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin
     di.max_lds = kLdsBytesPerWorkgroup;
   }
   SweepPlan P;
-  int rc = plan_sweep(sp, m, begin, count, mode, k, index_list != nullptr, di, &P);
+  int rc = plan_sweep(sp, m, begin, count, mode, k, merge != 0, index_list != nullptr, di, &P);
   if (rc) return rc;
   const Shape& sh = P.sh;
   const Variant* var = P.var;
@@ -990,8 +992,8 @@ static int run_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin
   }
 
   if (mode == MODE_TOPK) {
-    // lists: pool 0..groups-1, then the running result
-    const uint32_t n_lists = groups + 1;
+    // lists: pool 0..groups-1, then the running result when the call merges with it
+    const uint32_t n_lists = P.n_lists;
     const size_t list_bytes = (size_t)L.kp * 8;
     bool finalized = false;
     if (P.merge_in_lds) {
@@ -1099,7 +1101,7 @@ int tuner_sweep_plan(const tuner_space* space, const tuner_model* model, uint64_
   if (k > TUNER_MAX_K) return set_error(TUNER_ETOOLARGE, "k > TUNER_MAX_K");
   tuner::SweepPlan P;
   const int rc = tuner::plan_sweep(space, model, index_begin, index_count, k > 0 ? tuner::MODE_TOPK : tuner::MODE_ALL,
-                                   k, false, tuner::device_info_or_default(), &P);
+                                   k, false, false, tuner::device_info_or_default(), &P);
   if (rc) return rc;
   tuner_sweep_plan_info info{};
   info.network = P.sh.net;

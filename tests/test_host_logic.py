@@ -229,10 +229,13 @@ def test_sweep_plan_of_the_benchmark_configurations():
     p = plan(wc, 0, wc.space.n_configs, 200)
     assert p["tiles_per_wave"] == 1 and p["workgroups"] == 256 and p["n_units"] == 256
     assert p["dynamic_queue"] == 0 and p["live_chunk_list"] == 0
-    # 257 lists of 256 keys: 9 workgroups merge 32 lists each, the last of them to finish merges
-    # the nine results in the same launch; lists of 1024 keys (k = 1000) take 257 -> 17, then 17 -> 2 -> 1
+    # (the plan is that of a call with merge = 0: the running result is not one of the lists)
+    # 256 lists of 256 keys: 8 workgroups merge 32 lists each, the last of them to finish merges
+    # the eight results in the same launch; lists of 1024 keys (k = 1000): 16 workgroups merge 16
+    # lists each and the last one the 16 results, which just fill its 128 KB
     assert p["merge_launches"] == 1
-    assert plan(wl.large(), 0, 1 << 27, 1000)["merge_launches"] == 2
+    assert plan(wl.large(), 0, 1 << 27, 1000)["merge_launches"] == 1
+    assert plan(wl.streamed(), 0, 1 << 28, 4096)["merge_launches"] == 3      # 256 -> 64 -> 16 -> 4 -> 1
     # an empty range launches no sweep
     p = plan(wc, 77, 0, 200)
     assert p["workgroups"] == 0 and p["n_chunks"] == 0
