@@ -31,8 +31,8 @@ PEAK_HBM_GBS = 8000.0
 # one profiling run: this script cannot read those counters; the summary of that run is the
 # file named beside the figure.
 TRAFFIC_SOURCE = "profiles/sweep_kernel_f32mfma_cfg3.md"
-TRAFFIC_BYTES = {("cfg3", "topk", "f32-mfma"): (2016.51 * 2.0 + 4073.63) * 1024.0,
-                 ("cfg3", "all", "f32-mfma"): 250358.0 * 1024.0}
+TRAFFIC_BYTES = {("cfg3", "topk", "f32-mfma"): (1943.17 * 2.0 + 3049.16) * 1024.0,
+                 ("cfg3", "all", "f32-mfma"): 249334.0 * 1024.0}
 CPU_THREADS_CAP = 16              # the host share that goes with one GPU on the benchmark boxes
 
 
