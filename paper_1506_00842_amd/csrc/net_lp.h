@@ -61,8 +61,15 @@ __device__ __forceinline__ void pack_pair(float a, float b, uint32_t& hi, uint32
   const V2 hv = __builtin_convertvector(ab, V2);
   hi = __builtin_bit_cast(uint32_t, hv);
   if constexpr (NPL == 2) {
-    const float2v r = {a - (float)hv[0], b - (float)hv[1]};
-    lo = __builtin_bit_cast(uint32_t, __builtin_convertvector(r, V2));
+    // a - hi as a fused multiply-add that reads the 16-bit half directly and rounds its
+    // fp32 result into one half of the word (v_fma_mixlo_f16 / v_fma_mixhi_f16): two
+    // instructions per pair instead of two conversions, two subtractions and a pack
+    // (the factor -1 sits in a register the compiler cannot see through: as a literal it would
+    // turn the multiply-add back into a subtraction of a converted value)
+    float m1 = -1.0f;
+    asm("" : "+v"(m1));
+    const V2 lv = {(T)__builtin_fmaf((float)hv[0], m1, a), (T)__builtin_fmaf((float)hv[1], m1, b)};
+    lo = __builtin_bit_cast(uint32_t, lv);
   } else {
     lo = 0u;
   }
