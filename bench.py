@@ -293,6 +293,15 @@ def main():
         graph.replay() if args.graph else step()
     torch.cuda.synchronize()
     ms_per_step_no_events = 1e3 * (time.perf_counter() - t0) / args.steps
+    # spread of the kernel's duration: the same steps once more, the events read after each one
+    per_step_ms = []
+    T.tuner_profile_enable(True)
+    for _ in range(args.steps):
+        step()
+        ms, nl = T.tuner_profile_read()
+        if nl:
+            per_step_ms.append(ms / nl)
+    T.tuner_profile_enable(False)
 
     ms_per_step = 1e3 * dt / args.steps
     n_valid = w.n_valid if w.n_valid >= 0 else None
@@ -300,6 +309,10 @@ def main():
     if roof is not None:
         tb = TRAFFIC_BYTES.get((args.workload, args.mode, args.net))
         roof["traffic"] = tb
+        if per_step_ms:
+            srt = sorted(per_step_ms)
+            roof["kernel_ms_median"] = srt[len(srt) // 2] if len(srt) % 2 else 0.5 * (srt[len(srt) // 2 - 1] + srt[len(srt) // 2])
+            roof["kernel_ms_min"], roof["kernel_ms_max"] = srt[0], srt[-1]
         roof["traffic_source"] = (f"{TRAFFIC_SOURCE} (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this command, a "
                                   "constant from that profiling run, not measured by this one)") if tb else None
     out = {
