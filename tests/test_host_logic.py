@@ -422,3 +422,51 @@ def test_bench_refuses_more_than_one_gpu():
                        text=True, timeout=120)
     assert r.returncode != 0
     assert "ONE GPU" in (r.stdout + r.stderr)
+
+
+def test_header_is_plain_c_and_the_documented_call_sequence_links(tmp_path):
+    """include/tuner.h compiles as C99 with warnings as errors, and a C program that makes the
+    documented call sequence links against the library and runs its host-only part (space
+    creation, size, workspace size, plan, error text) without a GPU."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    src = tmp_path / "use_tuner.c"
+    src.write_text(r'''
+#include <stdio.h>
+#include <string.h>
+#include "tuner.h"
+int main(void) {
+  const int32_t radices[3] = {4, 2, 8};
+  const double values[14] = {1, 2, 4, 8, 0, 1, 1, 2, 3, 4, 5, 6, 7, 8};
+  const int32_t scales[3] = {TUNER_SCALE_LOG2, TUNER_SCALE_LINEAR, TUNER_SCALE_LINEAR};
+  const int32_t terms[14] = {0, 1, 2, 3, 0, 0, 0, 0, 0, 0, 0, 0, 1, 1};
+  const int64_t bounds[1] = {3};
+  tuner_space* space = NULL;
+  if (tuner_space_create(3, radices, values, scales, 1, terms, bounds, &space) != TUNER_OK) return 1;
+  uint64_t n = 0;
+  if (tuner_space_size(space, &n) != TUNER_OK || n != 64) return 2;
+  int32_t widths[3] = {3, 30, 1};
+  float fake;                      /* never dereferenced on the host */
+  tuner_model model = {11, 2, widths, &fake, TUNER_FP32, TUNER_ALGO_AUTO};
+  size_t ws = tuner_workspace_bytes(space, &model, 10);
+  if (ws == 0) return 3;
+  tuner_sweep_plan_info info;
+  if (tuner_sweep_plan(space, &model, 0, n, 10, &info) != TUNER_OK || info.workgroups < 1) return 4;
+  /* a call that must fail on the host, before any GPU work: no workspace */
+  int rc = tuner_predict_topk(space, &model, 0, n, 10, 0, &fake, (uint32_t*)&fake, (int32_t*)&fake, NULL, 0, NULL);
+  if (rc != TUNER_EWORKSPACE || strlen(tuner_last_error()) == 0) return 5;
+  printf("n=%llu ws=%zu workgroups=%d version=%s\n", (unsigned long long)n, ws, info.workgroups, tuner_version());
+  tuner_space_destroy(space);
+  return 0;
+}
+''')
+    exe = tmp_path / "use_tuner"
+    lib_dir = os.path.dirname(T.LIB_PATH)
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(root, "include"),
+                    str(src), "-o", str(exe), "-L", lib_dir, "-l:" + os.path.basename(T.LIB_PATH),
+                    "-Wl,-rpath," + lib_dir], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout
+    assert out.startswith("n=64 ws=") and "workgroups=" in out
