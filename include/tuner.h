@@ -279,6 +279,7 @@ int tuner_predict_all_prepared(const tuner_space* space, const tuner_model* mode
  *   - Every call on a GPU uses that GPU's one array: calls that may run at the
  *     same time on one GPU (different streams, different threads) race.  Calls
  *     ordered on one stream are safe; nothing needs to be cleared between them.
+ *   - It is not timed by tuner_profile_enable (timing creates HIP events).
  */
 #define TUNER_STATIC_SCRATCH_BYTES (64u << 20)
 int tuner_predict_topk_static(const tuner_space* space, const tuner_model* model,

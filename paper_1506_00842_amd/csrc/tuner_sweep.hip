@@ -861,7 +861,7 @@ static int plan_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begi
 static int run_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin, uint64_t count,
                      int mode, int k, int merge, float* values, uint32_t* indices, int32_t* n_found,
                      float* pred, uint8_t* mask, void* ws, size_t ws_bytes, hipStream_t stream,
-                     const uint32_t* index_list = nullptr, bool prepared = false) {
+                     const uint32_t* index_list = nullptr, bool prepared = false, bool timed = true) {
   // ---- everything that can fail comes before the first launch
   // (argument errors are reported even where there is no device to ask: the plan then uses
   // MI355X's figures and the device error comes after them)
@@ -890,7 +890,7 @@ static int run_sweep(const tuner_space* sp, const tuner_model* m, uint64_t begin
     if (rc) return rc;
   }
   hipEvent_t ev0 = nullptr, ev1 = nullptr;
-  if (g_profile.on && P.groups > 0) {
+  if (g_profile.on && timed && P.groups > 0) {
     TUNER_HIP_TRY(hipEventCreate(&ev0));
     const hipError_t e = hipEventCreate(&ev1);
     if (e != hipSuccess) { (void)hipEventDestroy(ev0); return hip_error(e, "hipEventCreate"); }
@@ -1255,7 +1255,8 @@ int tuner_predict_topk_static(const tuner_space* space, const tuner_model* model
   if (rc) return rc;
   return tuner::run_sweep(space, model, index_begin, index_count, tuner::MODE_TOPK, k,
                           merge_with_existing ? 1 : 0, topk_values_dev, topk_indices_dev, n_found_dev,
-                          nullptr, nullptr, ws, (size_t)TUNER_STATIC_SCRATCH_BYTES, (hipStream_t)hip_stream);
+                          nullptr, nullptr, ws, (size_t)TUNER_STATIC_SCRATCH_BYTES, (hipStream_t)hip_stream,
+                          nullptr, false, /*timed=*/false);   // creates no events either
 }
 
 int tuner_predict_all(const tuner_space* space, const tuner_model* model, uint64_t index_begin,

@@ -113,6 +113,27 @@ def test_static_scratch_chunked_running_result_and_other_networks():
         assert int(s.n_found.item()) == 0
 
 
+def test_static_scratch_call_records_no_timing_events():
+    """Timing a call means creating HIP events; the call that allocates nothing creates none,
+    also while timing is switched on (the plain call beside it records one pair)."""
+    import paper_1506_00842_amd as T
+    w = wl.conv_shaped()
+    s = StaticTopk(w)
+    T.tuner_profile_enable(True)
+    try:
+        T.tuner_profile_read()
+        s.topk(0, w.space.n_configs)
+        torch.cuda.synchronize()
+        assert T.tuner_profile_pending() == 0
+        s.ref.topk(0, w.space.n_configs)
+        torch.cuda.synchronize()
+        assert T.tuner_profile_pending() == 1
+        s.same_as_reference()
+    finally:
+        T.tuner_profile_enable(False)
+    assert T.tuner_profile_pending() == 0
+
+
 def test_static_scratch_refuses_what_does_not_fit():
     import paper_1506_00842_amd as T
     w = wl.large()
